@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the CCE- hot path on one MI355X: forward + backward of the loss over one synthetic batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--algo auto|gather|tile]
+
+A step is one cce_neg_forward followed by one cce_neg_backward on inputs already resident in HBM.  The line printed on
+stdout is one JSON object: whole-job positions/s, the roofline of the dominant kernel (timed with events on the launch
+stream inside the timed region), and the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+PEAK_F32_VALU_TFLOPS = 157.3
+
+
+def algorithmic_work(w):
+    """Flops and minimum HBM bytes of one forward+backward, counted on valid positions only.
+
+    flops: four GEMM-equivalents (scores forward, scores recomputed, dH, dE), 2 flop per multiply-add:
+           8 * n_cand * d per valid position, n_cand = K+1 (or V for the full catalogue).
+    bytes: every operand the method must move once: H read in both passes, the gathered candidate rows in both passes,
+           dH written, dE rows written once (write-once accounting), ids, per-position vectors.
+    """
+    nv = w.n_valid
+    esz = 4 if w.in_dtype == "f32" else 2
+    n_cand = w.V if w.neg_mode == 2 else w.K + 1
+    flops = 8.0 * n_cand * w.d * nv
+    row = w.d * esz
+    if w.neg_mode == 1:      # per-position: every candidate row is fetched per position, twice; dE rows written once each
+        gathered = 2.0 * nv * n_cand * row
+        dE_bytes = float(nv) * n_cand * w.d * 4
+        ids = 2.0 * nv * w.K * 4
+    else:                    # shared / full: the candidate block is read once per pass, target rows per position
+        n_neg_rows = w.V if w.neg_mode == 2 else w.K
+        gathered = 2.0 * (n_neg_rows * row + (nv * row if w.neg_mode == 0 else 0))
+        dE_bytes = float(n_neg_rows) * w.d * 4 + (float(nv) * w.d * 4 if w.neg_mode == 0 else 0)
+        ids = 2.0 * (w.K * 4 if w.neg_mode == 0 else 0)
+    per_pos = nv * (2 * row + w.d * 4) + w.N * (4 + 1 + 4 * 4)   # H twice, dH fp32, tgt, mask, loss/lse/lse/g
+    return flops, gathered + dE_bytes + ids + per_pos
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the config the metric is quoted on)")
+    ap.add_argument("--algo", default="auto", choices=["auto", "gather", "tile"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists for the product path)", file=sys.stderr)
+        return 2
+
+    import paper_2509_09682_amd as P
+    from hip_harness import to_device
+    from workloads import config
+
+    w = config(args.config)
+    H, E, tgt, neg, mask = to_device(w)
+    algo = {"auto": P.CCE_ALGO_AUTO, "gather": P.CCE_ALGO_GATHER, "tile": P.CCE_ALGO_TILE}[args.algo]
+    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
+                       mask_target_collisions=w.mask_collisions, validate_indices=0, algo=algo)
+    ws = P.new_workspace(desc)
+    loss = torch.empty(w.N, device="cuda")
+    lse = torch.empty(w.N, device="cuda")
+    g = torch.from_numpy(w.g).cuda()
+    dH = torch.empty((w.N, w.d), device="cuda")
+    dE = torch.zeros((w.V, w.d), device="cuda")
+
+    def step():
+        P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: K steps bracketed by synchronisation; events on the launch stream split forward and backward
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        ev[k][1].record()
+        P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    # dE zero-fill, reported apart from the step (dE is an accumulate-into buffer owned by the caller)
+    z0, z1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    z0.record()
+    dE.zero_()
+    z1.record()
+    torch.cuda.synchronize()
+    memset_ms = z0.elapsed_time(z1)
+
+    flops, bytes_min = algorithmic_work(w)
+    gather_bound = (w.neg_mode == 1)
+    # dominant launch = the backward call (3 of the 4 GEMM-equivalents; all of the dE traffic)
+    if gather_bound:
+        _, b_all = algorithmic_work(w)
+        # backward's share of the bytes: one gather pass + dE + dH + half of the per-position vectors
+        esz = 4 if w.in_dtype == "f32" else 2
+        n_cand = w.K + 1
+        b_bwd = w.n_valid * n_cand * w.d * esz + w.n_valid * n_cand * w.d * 4 + w.n_valid * w.K * 4 \
+            + w.n_valid * (w.d * esz + w.d * 4) + w.N * 13
+        roof = {"bound": "hbm", "kernel": "backward", "achieved": b_bwd / (bwd_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "traffic": None}
+    else:
+        f_bwd = flops * 0.75
+        roof = {"bound": "mfma", "kernel": "backward", "achieved": f_bwd / (bwd_ms * 1e-3) / 1e12,
+                "peak": PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS, "unit": "TFLOP/s",
+                "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["avg_launch_ms"] = bwd_ms
+
+    out = {
+        "metric": "CE- fwd+bwd positions/sec at 1 GPU",
+        "value": w.N / (ms_step * 1e-3),
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if w.in_dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
+            "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
+            "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
+            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "dE_zero_fill_ms": memset_ms,
+            "algorithmic_gflop": flops / 1e9, "algorithmic_mbytes": bytes_min / 1e6,
+            "whole_step_tflops": flops / (ms_step * 1e-3) / 1e12,
+            "whole_step_frac_mfma_peak": flops / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+            "hbm_bytes": {"inputs": int(H.numel() * H.element_size() + E.numel() * E.element_size() + tgt.numel() * 4
+                                        + (0 if neg is None else neg.numel() * 4) + w.N),
+                          "outputs": int(w.N * 8 + dH.numel() * 4 + dE.numel() * 4),
+                          "workspace": int(ws.numel()),
+                          "torch_peak_allocated": int(torch.cuda.max_memory_allocated())},
+        },
+        "roofline": roof,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import cce_oracle as O
+
+        valid_idx = np.flatnonzero(w.mask)
+        pilot = valid_idx[: min(64, valid_idx.size)].astype(np.int64)
+        t = time.perf_counter()
+        O.run_workload(w, sel=pilot, want_dE="compact")
+        dt = max(time.perf_counter() - t, 1e-4)
+        n_sample = int(min(valid_idx.size, max(64, args.cpu_seconds / (dt / pilot.size))))
+        sample = valid_idx[:n_sample].astype(np.int64)
+        t = time.perf_counter()
+        O.run_workload(w, sel=sample, want_dE="compact")
+        dt = time.perf_counter() - t
+        # scale to the metric's unit: positions as passed (padded ones cost the oracle nothing)
+        out["cpu_baseline"] = {
+            "value": (n_sample / dt) * (w.N / max(w.n_valid, 1)), "unit": "positions/s", "cores": O.num_threads(),
+            "kind": "oracle", "sample": f"first {n_sample} valid positions of {w.name} (fwd+bwd, fp64, {dt:.1f} s)",
+        }
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

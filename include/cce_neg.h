@@ -1,0 +1,127 @@
+/*
+ * cce_neg.h - C ABI of the fused cross-entropy loss with negative sampling (CCE-)
+ * for AMD MI355X (gfx950).
+ *
+ * The operation is the paper's Sec. 3.3 ("Cut-Cross-Entropy with Negative
+ * Sampling"): for every position i of the flattened final-layer output H [N,d]
+ * (the paper's E), score it against its correct item and K sampled negative items
+ * taken from the item table E [V,d] (the paper's classifier C, stored row-major
+ * as C^T), and return
+ *
+ *     lse_i  = log sum_j exp(<H_i, E_{c_ij}>)         (Eq. 5, indexed log-sum-exp)
+ *     loss_i = lse_i - <H_i, E_{tgt_i}>               (Eq. 4, per position, l = o+ - LSE, L = -mean l)
+ *
+ * without ever writing the [N x (K+1)] score matrix to device memory (Alg. 1).
+ * The backward call recomputes the scores, forms the softmax S = exp(o - LSE)
+ * and returns dH and the scatter-added dE (Eq. 6, Alg. 2), folding in the
+ * gradient of the correct-item score (the first term of Eq. 4).  The
+ * full-catalogue mode is the paper's Sec. 3.1 loss (Eq. 2): all V items are the
+ * candidates, no sampling, no gradient filtering.
+ *
+ * All pointers are DEVICE pointers owned by the caller, row-major, contiguous and
+ * 16-byte aligned.  The library allocates and frees nothing.  Work is enqueued on
+ * the HIP stream passed in (hipStream_t as void*, NULL = default stream) and the
+ * calls return without synchronising.  Scalars of the mean reduction (Eq. 3) are
+ * the caller's business: pass grad_loss[i] = 1/N_valid for a mean loss.
+ */
+#ifndef CCE_NEG_H
+#define CCE_NEG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CCE_OK = 0,
+    CCE_ERR_NULL = 1,        /* a required pointer is NULL */
+    CCE_ERR_SHAPE = 2,       /* N < 0, V <= 0, K < 0, d not a multiple of 8 in [8,512], V or K beyond int32 */
+    CCE_ERR_DTYPE = 3,       /* unknown dtype, or dH_dtype = BF16 with fp32 inputs */
+    CCE_ERR_INDEX = 4,       /* an id of a valid position was outside [0,V) (reported by cce_neg_index_status) */
+    CCE_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than cce_neg_workspace_bytes() */
+    CCE_ERR_UNSUPPORTED = 6, /* the requested algo cannot run this descriptor */
+    CCE_ERR_HIP = 7          /* a HIP runtime call (launch) failed */
+} cce_status;
+
+typedef enum { CCE_F32 = 0, CCE_BF16 = 1 } cce_dtype;
+
+typedef enum {
+    CCE_NEG_SHARED = 0,       /* neg is [K]: one list of negatives for all positions */
+    CCE_NEG_PER_POSITION = 1, /* neg is [N,K]: row i holds the negatives of position i (the paper's Inds without its first column) */
+    CCE_NEG_FULL = 2          /* neg ignored: all V items are candidates (Sec. 3.1, Eq. 2) */
+} cce_neg_mode;
+
+typedef enum {
+    CCE_ALGO_AUTO = 0,   /* library picks: MFMA tiles for bf16 shared/full, row gathers otherwise */
+    CCE_ALGO_GATHER = 1, /* one wavefront per position, candidate rows gathered one by one (Alg. 1 / Alg. 2 as printed) */
+    CCE_ALGO_TILE = 2    /* dense H x E_neg^T score tiles on the matrix cores; bf16 inputs, shared or full mode only */
+} cce_algo;
+
+typedef struct {
+    int64_t N;                      /* positions = batch * sequence length (Sec. 3.1) */
+    int64_t V;                      /* catalogue size, rows of E */
+    int32_t d;                      /* hidden size; multiple of 8, 8..512; never split (Sec. 3.3) */
+    int32_t K;                      /* negatives per position (the paper's ns); ignored for CCE_NEG_FULL; 0 allowed */
+    int32_t in_dtype;               /* cce_dtype of H and E */
+    int32_t dH_dtype;               /* cce_dtype of dH: F32, or BF16 (round-to-nearest-even) when in_dtype is BF16 */
+    int32_t neg_mode;               /* cce_neg_mode */
+    int32_t mask_target_collisions; /* 1: a negative equal to the position's own target is left out of LSE and gradients */
+    int32_t validate_indices;       /* 1: kernels range-check ids of valid positions, skip bad ones and raise the status word */
+    int32_t algo;                   /* cce_algo */
+} cce_desc;
+
+/* Bytes of device workspace both calls need for this descriptor: O(N + K*d), never O(N*K).
+ * Returns 0 for an invalid descriptor.  The same workspace may be reused by later calls on the same stream. */
+size_t cce_neg_workspace_bytes(const cce_desc *desc);
+
+/* Clears the workspace header (index status word).  Call once after allocating a workspace, on the stream that will
+ * use it; enqueues a small fill kernel (no memset node, so it is safe under stream capture). */
+cce_status cce_neg_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Forward (Alg. 1; Eq. 4, Eq. 5).
+ *   H     [N,d]  in_dtype          hidden states
+ *   E     [V,d]  in_dtype          item table
+ *   tgt   [N]    int32             correct item per position (first column of the paper's Inds)
+ *   neg   [K] or [N,K] int32       negatives (NULL allowed when K == 0 or mode FULL); duplicates count once each
+ *   mask  [N]    uint8, nullable   1 = valid, 0 = padding; NULL = all valid.  For a padded position loss = lse = +0
+ *                                  and its tgt / neg entries are never read.
+ *   loss  [N]    float  (out)      lse_i - o+_i, fully overwritten
+ *   lse   [N]    float  (out)      fully overwritten; feed it to cce_neg_backward
+ * Host-checkable errors are returned before anything is launched and nothing is written.
+ */
+cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
+                           const uint8_t *mask, float *loss, float *lse, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+
+/*
+ * Backward (Alg. 2; Eq. 6; S = exp(o - LSE)).
+ *   lse        [N] float            from the forward call on the same inputs
+ *   grad_loss  [N] float, nullable  upstream gradient of loss_i (the paper's grad LSE); NULL = 1
+ *   dH  [N,d] dH_dtype (out)        fully overwritten, rows of padded positions are zero
+ *   dE  [V,d] float (in/out)        ACCUMULATED INTO with floating-point atomics: the caller zeroes it or carries
+ *                                   earlier gradients; rows that no valid position indexes are left untouched
+ * With G_ij = grad_loss_i * (softmax_ij - [j is the correct item]):
+ *   dH_i = sum_j G_ij E_{c_ij},   dE_{c_ij} += G_ij H_i.
+ */
+cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
+                            const uint8_t *mask, const float *lse, const float *grad_loss, void *dH, float *dE,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Synchronises hip_stream and reads the index status word kept in workspace.  Returns CCE_ERR_INDEX if any call on
+ * that workspace since the last query found an id outside [0,V) on a valid position (validate_indices = 1 only),
+ * CCE_OK otherwise; the word is cleared.  Bad ids are never dereferenced: a bad negative is skipped, a position with a
+ * bad target is treated as padding.
+ */
+cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *cce_status_string(cce_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCE_NEG_H */

@@ -1,0 +1,132 @@
+"""ctypes binding of libcce_neg.so: argument marshalling only, every step runs in the HIP kernels.
+
+Tensors are torch CUDA tensors used as device allocations; kernels are enqueued on torch's current stream.
+There is no CPU fallback: a missing library or a missing GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcce_neg.so")
+
+CCE_OK = 0
+CCE_ERR_NULL, CCE_ERR_SHAPE, CCE_ERR_DTYPE, CCE_ERR_INDEX = 1, 2, 3, 4
+CCE_ERR_WORKSPACE, CCE_ERR_UNSUPPORTED, CCE_ERR_HIP = 5, 6, 7
+CCE_F32, CCE_BF16 = 0, 1
+CCE_NEG_SHARED, CCE_NEG_PER_POSITION, CCE_NEG_FULL = 0, 1, 2
+CCE_ALGO_AUTO, CCE_ALGO_GATHER, CCE_ALGO_TILE = 0, 1, 2
+
+EXPORTS = (
+    "cce_neg_workspace_bytes", "cce_neg_workspace_init", "cce_neg_forward", "cce_neg_backward",
+    "cce_neg_index_status", "cce_status_string",
+)
+
+
+class CceDesc(ctypes.Structure):
+    _fields_ = [
+        ("N", ctypes.c_int64), ("V", ctypes.c_int64), ("d", ctypes.c_int32), ("K", ctypes.c_int32),
+        ("in_dtype", ctypes.c_int32), ("dH_dtype", ctypes.c_int32), ("neg_mode", ctypes.c_int32),
+        ("mask_target_collisions", ctypes.c_int32), ("validate_indices", ctypes.c_int32), ("algo", ctypes.c_int32),
+    ]
+
+
+class CceError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built (python -m paper_2509_09682_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_09682_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+        L.cce_neg_workspace_bytes.restype = ctypes.c_size_t
+        L.cce_neg_workspace_bytes.argtypes = [ctypes.POINTER(CceDesc)]
+        L.cce_neg_workspace_init.restype = ctypes.c_int
+        L.cce_neg_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
+        L.cce_neg_forward.restype = ctypes.c_int
+        L.cce_neg_forward.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.cce_neg_backward.restype = ctypes.c_int
+        L.cce_neg_backward.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
+                                       ctypes.c_size_t, vp]
+        L.cce_neg_index_status.restype = ctypes.c_int
+        L.cce_neg_index_status.argtypes = [vp, ctypes.c_size_t, vp]
+        L.cce_status_string.restype = ctypes.c_char_p
+        L.cce_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().cce_status_string(int(status)).decode()
+
+
+def make_desc(N: int, V: int, d: int, K: int, in_dtype: int, neg_mode: int, *, dH_dtype: Optional[int] = None,
+              mask_target_collisions: int = 1, validate_indices: int = 0, algo: int = CCE_ALGO_AUTO) -> CceDesc:
+    return CceDesc(int(N), int(V), int(d), int(K), int(in_dtype), int(CCE_F32 if dH_dtype is None else dH_dtype),
+                   int(neg_mode), int(mask_target_collisions), int(validate_indices), int(algo))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors handed to the CCE- library must be contiguous CUDA tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def cce_neg_workspace_bytes(desc: CceDesc) -> int:
+    return int(lib().cce_neg_workspace_bytes(ctypes.byref(desc)))
+
+
+def cce_neg_workspace_init(workspace: torch.Tensor) -> None:
+    st = lib().cce_neg_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if st != CCE_OK:
+        raise CceError(st, "cce_neg_workspace_init")
+
+
+def new_workspace(desc: CceDesc, device="cuda") -> torch.Tensor:
+    n = cce_neg_workspace_bytes(desc)
+    if n == 0:
+        raise CceError(CCE_ERR_SHAPE, "cce_neg_workspace_bytes")
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    cce_neg_workspace_init(ws)
+    return ws
+
+
+def cce_neg_forward(desc: CceDesc, H, E, tgt, neg, mask, loss, lse, workspace, *, check: bool = True) -> int:
+    st = lib().cce_neg_forward(ctypes.byref(desc), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg), _ptr(mask), _ptr(loss),
+                               _ptr(lse), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_forward")
+    return st
+
+
+def cce_neg_backward(desc: CceDesc, H, E, tgt, neg, mask, lse, grad_loss, dH, dE, workspace, *, check: bool = True) -> int:
+    st = lib().cce_neg_backward(ctypes.byref(desc), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg), _ptr(mask), _ptr(lse),
+                                _ptr(grad_loss), _ptr(dH), _ptr(dE), _ptr(workspace),
+                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_backward")
+    return st
+
+
+def cce_neg_index_status(workspace: torch.Tensor) -> int:
+    return int(lib().cce_neg_index_status(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))

@@ -1,0 +1,78 @@
+// Shared device-side helpers and the kernel parameter block of the CCE- library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cce_neg.h"
+
+namespace cce {
+
+// Everything a kernel needs, passed by value at launch.
+struct Params {
+    const void *H;          // [N,d] in_dtype
+    const void *E;          // [V,d] in_dtype
+    const int32_t *tgt;     // [N]
+    const int32_t *neg;     // [K] | [N,K] | nullptr
+    const uint8_t *mask;    // [N] | nullptr
+    const float *lse_in;    // [N] (backward)
+    const float *g;         // [N] | nullptr (backward)
+    float *loss;            // [N] (forward)
+    float *lse;             // [N] (forward)
+    void *dH;               // [N,d] (backward)
+    float *dE;              // [V,d] (backward)
+    int32_t *status;        // index status word in the workspace header
+    int64_t N, V;
+    int32_t d, K;
+    int32_t neg_mode, collide, validate, dH_bf16;
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// float -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// Load 8 consecutive elements (16-byte aligned for bf16, 32-byte for fp32) and widen to float.
+__device__ __forceinline__ void load8(const float *p, float (&v)[8])
+{
+    const float4 a = reinterpret_cast<const float4 *>(p)[0];
+    const float4 b = reinterpret_cast<const float4 *>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const uint16_t *p, float (&v)[8])
+{
+    const uint4 r = *reinterpret_cast<const uint4 *>(p);
+    v[0] = bf16_lo(r.x); v[1] = bf16_hi(r.x);
+    v[2] = bf16_lo(r.y); v[3] = bf16_hi(r.y);
+    v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z);
+    v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
+}
+__device__ __forceinline__ float load1(const float *p) { return *p; }
+__device__ __forceinline__ float load1(const uint16_t *p) { return __uint_as_float(static_cast<uint32_t>(*p) << 16); }
+
+// exp(x) and log(x) through the base-2 hardware units.
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
+
+// Merge two (max, sum-of-exp) pairs of an online softmax; either may be the empty pair (-inf, 0).
+__device__ __forceinline__ void lse_merge(float &m, float &s, float m2, float s2)
+{
+    const float M = fmaxf(m, m2);
+    if (M == -INFINITY) { s = 0.f; return; }
+    s = s * fast_exp(m - M) + s2 * fast_exp(m2 - M);
+    m = M;
+}
+
+}  // namespace cce

@@ -1,0 +1,266 @@
+// Row-gather kernels: one wavefront per position, candidate rows fetched one by one.
+//
+// This is the data access scheme of the paper's Alg. 1 / Alg. 2 as printed: for a block of positions, walk the
+// candidate columns j of the index matrix, load the indexed item rows, take the scalar product over the whole hidden
+// dimension (never split, Sec. 3.3), and keep the running max / sum of the online softmax on chip.  It serves every
+// mode and dtype; it is the fast path for per-position negatives (a batched GEMV with no operand reuse, bound by the
+// row gathers) and the exact-fp32 path.
+//
+// Lane layout: a row of d elements is covered by LPR lanes, 8 consecutive elements (one 16-byte bf16 load) per lane, so
+// a wavefront scores 64/LPR candidates per load instruction and UNROLL of those are in flight together.  The dot
+// product is finished with a butterfly over the LPR lanes.  dE updates use a second, interleaved column mapping
+// (lane c owns columns c, c+LPR, ...) so that one atomic instruction covers consecutive addresses of the row.
+#include "cce_device.hpp"
+#include "cce_kernels.hpp"
+
+namespace cce {
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kUnroll = 4;
+
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Candidate j of position i: id, whether it is the correct item, whether it takes part.
+struct Cand {
+    int64_t id;
+    bool is_pos;
+    bool live;
+};
+
+__device__ __forceinline__ Cand candidate(const Params &p, int64_t i, int64_t j, int64_t n_cand, int32_t ti, bool &bad)
+{
+    Cand c{0, false, false};
+    if (j >= n_cand) return c;
+    if (p.neg_mode == CCE_NEG_FULL) {
+        c.id = j;
+        c.is_pos = (j == ti);
+        c.live = true;
+        return c;
+    }
+    if (j == 0) {
+        c.id = ti;
+        c.is_pos = true;
+        c.live = true;
+        return c;
+    }
+    const int32_t id = (p.neg_mode == CCE_NEG_SHARED) ? p.neg[j - 1] : p.neg[i * (int64_t)p.K + (j - 1)];
+    c.id = id;
+    c.live = !(p.collide && id == ti);
+    if (p.validate && (id < 0 || (int64_t)id >= p.V)) {
+        c.live = false;
+        bad = true;
+    }
+    return c;
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params p)
+{
+    constexpr int RPI = 64 / LPR;  // candidate rows per wavefront step
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int grp = lane / LPR;
+    const int64_t i = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (i >= p.N) return;
+
+    bool valid = (p.mask == nullptr) || (p.mask[i] != 0);
+    int32_t ti = 0;
+    bool bad = false;
+    if (valid) {
+        ti = p.tgt[i];
+        if (p.validate && (ti < 0 || (int64_t)ti >= p.V)) { bad = true; valid = false; }
+    }
+    if (!valid) {
+        if (lane == 0) {
+            p.loss[i] = 0.f;
+            p.lse[i] = 0.f;
+            if (bad) atomicOr(p.status, 1);
+        }
+        return;
+    }
+
+    const T *Hp = static_cast<const T *>(p.H);
+    const T *Ep = static_cast<const T *>(p.E);
+    const bool col_ok = (c * 8 < p.d);
+    float h[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) h[t] = 0.f;
+    if (col_ok) load8(Hp + i * (int64_t)p.d + c * 8, h);
+
+    const int64_t n_cand = (p.neg_mode == CCE_NEG_FULL) ? p.V : (int64_t)p.K + 1;
+    float m = -INFINITY, s = 0.f, o_pos = 0.f;
+
+    for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
+        Cand cd[kUnroll];
+        float e[kUnroll][8];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            cd[u] = candidate(p, i, j0 + u * RPI + grp, n_cand, ti, bad);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
+            if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float part = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[u][t], part);
+            const float o = group_sum<LPR>(part);
+            if (cd[u].live) {
+                if (cd[u].is_pos) o_pos = o;
+                const float mn = fmaxf(m, o);
+                s = s * fast_exp(m - mn) + fast_exp(o - mn);  // first live step: exp(-inf) = 0
+                m = mn;
+            }
+        }
+    }
+    // combine the 64/LPR candidate groups
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m, off, 64);
+        const float s2 = __shfl_xor(s, off, 64);
+        lse_merge(m, s, m2, s2);
+        o_pos += __shfl_xor(o_pos, off, 64);
+    }
+    if (p.validate && __any(bad)) {
+        if (lane == 0) atomicOr(p.status, 1);
+    }
+    if (lane == 0) {
+        const float l = m + fast_log(s);
+        p.lse[i] = l;
+        p.loss[i] = l - o_pos;
+    }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params p)
+{
+    constexpr int RPI = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int grp = lane / LPR;
+    const int64_t i = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (i >= p.N) return;
+
+    const bool col_ok = (c * 8 < p.d);
+    bool valid = (p.mask == nullptr) || (p.mask[i] != 0);
+    int32_t ti = 0;
+    bool bad = false;
+    if (valid) {
+        ti = p.tgt[i];
+        if (p.validate && (ti < 0 || (int64_t)ti >= p.V)) { bad = true; valid = false; }
+    }
+    float acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+
+    if (valid) {
+        const T *Hp = static_cast<const T *>(p.H);
+        const T *Ep = static_cast<const T *>(p.E);
+        float h[8], h2[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            h[t] = 0.f;
+            const int col = c + LPR * t;
+            h2[t] = (col < p.d) ? load1(Hp + i * (int64_t)p.d + col) : 0.f;
+        }
+        if (col_ok) load8(Hp + i * (int64_t)p.d + c * 8, h);
+        const float lse = p.lse_in[i];
+        const float gi = p.g ? p.g[i] : 1.f;
+        const int64_t n_cand = (p.neg_mode == CCE_NEG_FULL) ? p.V : (int64_t)p.K + 1;
+
+        for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
+            Cand cd[kUnroll];
+            float e[kUnroll][8];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                cd[u] = candidate(p, i, j0 + u * RPI + grp, n_cand, ti, bad);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
+                if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float part = 0.f;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[u][t], part);
+                const float o = group_sum<LPR>(part);
+                if (cd[u].live) {
+                    const float pj = fast_exp(o - lse);
+                    const float G = gi * (pj - (cd[u].is_pos ? 1.f : 0.f));
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, e[u][t], acc[t]);
+                    float *row = p.dE + cd[u].id * (int64_t)p.d;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        const int col = c + LPR * t;
+                        if (col < p.d) unsafeAtomicAdd(row + col, G * h2[t]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc[t] += __shfl_xor(acc[t], off, 64);
+        }
+    }
+    if (p.validate && __any(bad)) {
+        if (lane == 0) atomicOr(p.status, 1);
+    }
+    if (grp == 0 && col_ok) {
+        if (p.dH_bf16) {
+            uint4 w;
+            w.x = pack_bf16x2(acc[0], acc[1]);
+            w.y = pack_bf16x2(acc[2], acc[3]);
+            w.z = pack_bf16x2(acc[4], acc[5]);
+            w.w = pack_bf16x2(acc[6], acc[7]);
+            *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(p.dH) + i * (int64_t)p.d + c * 8) = w;
+        } else {
+            float4 *out = reinterpret_cast<float4 *>(static_cast<float *>(p.dH) + i * (int64_t)p.d + c * 8);
+            out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        }
+    }
+}
+
+template <typename T, int LPR>
+hipError_t launch_pair(bool backward, const Params &p, hipStream_t stream)
+{
+    if (p.N == 0) return hipSuccess;
+    const dim3 block(kWavesPerBlock * 64);
+    const dim3 grid((unsigned)((p.N + kWavesPerBlock - 1) / kWavesPerBlock));
+    if (backward)
+        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
+    else
+        hipLaunchKernelGGL((fwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_by_width(bool backward, const Params &p, hipStream_t stream)
+{
+    const int chunks = (p.d + 7) / 8;
+    if (chunks <= 2) return launch_pair<T, 2>(backward, p, stream);
+    if (chunks <= 4) return launch_pair<T, 4>(backward, p, stream);
+    if (chunks <= 8) return launch_pair<T, 8>(backward, p, stream);
+    if (chunks <= 16) return launch_pair<T, 16>(backward, p, stream);
+    if (chunks <= 32) return launch_pair<T, 32>(backward, p, stream);
+    return launch_pair<T, 64>(backward, p, stream);
+}
+
+}  // namespace
+
+hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream)
+{
+    return bf16 ? launch_by_width<uint16_t>(backward, p, stream) : launch_by_width<float>(backward, p, stream);
+}
+
+}  // namespace cce

@@ -1,0 +1,54 @@
+"""Runs a workload through the C ABI (via the ctypes binding) and returns numpy results.  GPU tests only."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+import paper_2509_09682_amd as P
+
+
+def to_device(w):
+    dev = "cuda"
+    if w.in_dtype == "f32":
+        H = torch.from_numpy(w.H).to(dev)
+        E = torch.from_numpy(w.E).to(dev)
+    else:  # uint16 bit patterns -> same bits in device memory
+        H = torch.from_numpy(w.H.view(np.int16)).to(dev)
+        E = torch.from_numpy(w.E.view(np.int16)).to(dev)
+    tgt = torch.from_numpy(w.tgt).to(dev)
+    neg = None if w.neg is None else torch.from_numpy(np.ascontiguousarray(w.neg)).to(dev)
+    mask = None if w.mask is None else torch.from_numpy(w.mask).to(dev)
+    return H, E, tgt, neg, mask
+
+
+def run_hip(w, *, g: Optional[np.ndarray] = "workload", algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32, validate=0,
+            use_mask=True, dE_init: Optional[np.ndarray] = None, repeat_backward: int = 1):
+    """Forward + backward on cuda:0.  Returns dict(loss, lse, dH (float32), dE (float32), status)."""
+    H, E, tgt, neg, mask = to_device(w)
+    if not use_mask:
+        mask = None
+    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
+                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate, algo=algo)
+    ws = P.new_workspace(desc)
+    loss = torch.full((w.N,), float("nan"), device="cuda")
+    lse = torch.full((w.N,), float("nan"), device="cuda")
+    P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+    if isinstance(g, str):
+        g_t = torch.from_numpy(w.g).to("cuda")
+    elif g is None:
+        g_t = None
+    else:
+        g_t = torch.from_numpy(np.asarray(g, np.float32)).to("cuda")
+    if dH_dtype == P.CCE_BF16:
+        dH = torch.full((w.N, w.d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    else:
+        dH = torch.full((w.N, w.d), float("nan"), device="cuda")
+    dE = torch.zeros((w.V, w.d), device="cuda") if dE_init is None else torch.from_numpy(dE_init).to("cuda")
+    for _ in range(repeat_backward):
+        P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g_t, dH, dE, ws)
+    status = P.cce_neg_index_status(ws)
+    torch.cuda.synchronize()
+    return dict(loss=loss.cpu().numpy(), lse=lse.cpu().numpy(), dH=dH.float().cpu().numpy(), dE=dE.cpu().numpy(),
+                status=status)

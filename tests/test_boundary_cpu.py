@@ -1,0 +1,82 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared symbol, and rejects bad
+arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2509_09682_amd import binding as B
+    from paper_2509_09682_amd import build
+
+    if not os.path.exists(B.LIB_PATH):
+        build.build()
+    return B
+
+
+def test_library_exports_every_declared_symbol(binding):
+    header = open(os.path.join(ROOT, "include", "cce_neg.h")).read()
+    declared = set(re.findall(r"\b(cce_neg_\w+|cce_status_string)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings(binding):
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes_rejects_bad_descriptors(binding):
+    B = binding
+    good = B.make_desc(512, 4096, 64, 128, B.CCE_F32, B.CCE_NEG_SHARED)
+    assert B.cce_neg_workspace_bytes(good) >= 256
+    for kw in (dict(N=-1), dict(V=0), dict(d=0), dict(d=12), dict(d=520), dict(K=-1), dict(in_dtype=5),
+               dict(neg_mode=3), dict(dH_dtype=B.CCE_BF16), dict(algo=9), dict(V=1 << 31)):
+        f = dict(N=512, V=4096, d=64, K=128, in_dtype=B.CCE_F32, neg_mode=B.CCE_NEG_SHARED, dH_dtype=B.CCE_F32, algo=0)
+        f.update(kw)
+        desc = B.make_desc(f["N"], f["V"], f["d"], f["K"], f["in_dtype"], f["neg_mode"], dH_dtype=f["dH_dtype"], algo=f["algo"])
+        assert B.cce_neg_workspace_bytes(desc) == 0, kw
+    # workspace stays O(N + K d): growing K or N by 10x must not grow it by the product
+    a = B.cce_neg_workspace_bytes(B.make_desc(51200, 50000, 64, 1024, B.CCE_BF16, B.CCE_NEG_SHARED))
+    b = B.cce_neg_workspace_bytes(B.make_desc(51200, 50000, 64, 10240, B.CCE_BF16, B.CCE_NEG_SHARED))
+    c = B.cce_neg_workspace_bytes(B.make_desc(512000, 50000, 64, 10240, B.CCE_BF16, B.CCE_NEG_SHARED))
+    assert b <= a + 10240 * 64 * 16 and c <= b + 512000 * 64 * 8
+
+
+def test_forward_backward_reject_null_and_small_workspace_before_launch(binding):
+    B = binding
+    L = B.lib()
+    desc = B.make_desc(16, 100, 64, 8, B.CCE_F32, B.CCE_NEG_SHARED)
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: every call below must fail on the host
+    st = L.cce_neg_forward(ctypes.byref(desc), None, fake, fake, fake, None, fake, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_NULL
+    st = L.cce_neg_forward(ctypes.byref(desc), fake, fake, fake, None, None, fake, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_NULL  # K > 0 needs neg
+    st = L.cce_neg_forward(ctypes.byref(desc), fake, fake, fake, fake, None, fake, fake, None, 4096, None)
+    assert st == B.CCE_ERR_WORKSPACE
+    st = L.cce_neg_forward(ctypes.byref(desc), fake, fake, fake, fake, None, fake, fake, fake, 8, None)
+    assert st == B.CCE_ERR_WORKSPACE
+    st = L.cce_neg_forward(ctypes.byref(desc), fake, fake, fake, fake, None, fake, fake, ctypes.c_void_p(0x1004), 4096, None)
+    assert st == B.CCE_ERR_WORKSPACE  # misaligned
+    st = L.cce_neg_forward(ctypes.byref(desc), fake, fake, fake, fake, None, None, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_NULL
+    st = L.cce_neg_backward(ctypes.byref(desc), fake, fake, fake, fake, None, None, None, fake, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_NULL  # lse missing
+    st = L.cce_neg_backward(ctypes.byref(desc), fake, fake, fake, fake, None, fake, None, fake, None, fake, 4096, None)
+    assert st == B.CCE_ERR_NULL  # dE missing
+    bad = B.make_desc(16, 100, 60, 8, B.CCE_F32, B.CCE_NEG_SHARED)
+    st = L.cce_neg_forward(ctypes.byref(bad), fake, fake, fake, fake, None, fake, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_SHAPE
+    bad = B.make_desc(16, 100, 64, 8, B.CCE_F32, B.CCE_NEG_SHARED, dH_dtype=B.CCE_BF16)
+    st = L.cce_neg_backward(ctypes.byref(bad), fake, fake, fake, fake, None, fake, None, fake, fake, fake, 4096, None)
+    assert st == B.CCE_ERR_DTYPE
+    assert L.cce_neg_workspace_init(None, 4096, None) == B.CCE_ERR_NULL
+    assert L.cce_neg_index_status(None, 4096, None) == B.CCE_ERR_NULL

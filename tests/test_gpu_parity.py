@@ -1,0 +1,150 @@
+"""Element-by-element parity of the HIP path (through the C ABI) against the fp64 oracle on seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle import cce_oracle as O
+from oracle.compare import per_position_rel, tensor_rel
+from workloads import NEG_FULL, NEG_PER_POSITION, NEG_SHARED, config, make_workload  # noqa: F401
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5    # fp32 path: relative error on loss, lse and gradients
+TOL_BF16 = 2e-2   # bf16 path
+
+
+def check_against_oracle(w, out, tol, *, g="workload", dE_init=None, dH_tol=None):
+    g_np = w.g if isinstance(g, str) else g
+    g64 = np.ones(w.N) if g_np is None else np.asarray(g_np, np.float64)   # a NULL grad_loss means 1
+    ref = O.run_workload(w, g=g64)
+    valid = w.mask != 0
+    # masked positions: exactly +0.0
+    for name in ("loss", "lse"):
+        assert np.all(out[name][~valid] == 0) and not np.any(np.signbit(out[name][~valid])), name
+    assert np.all(out["dH"][~valid] == 0)
+    e_loss = per_position_rel(out["loss"][valid], ref.loss[valid], ref.lse[valid], ref.loss[valid])
+    e_lse = per_position_rel(out["lse"][valid], ref.loss[valid], ref.lse[valid], ref.lse[valid])
+    e_dH = tensor_rel(out["dH"], ref.dH)
+    rows = O.touched_rows(w.tgt, w.neg, w.mask, w.neg_mode, w.V, mask_collisions=w.mask_collisions)
+    base = np.zeros_like(out["dE"]) if dE_init is None else dE_init
+    e_dE = tensor_rel((out["dE"].astype(np.float64) - base)[rows], ref.dE[rows])
+    # rows nobody indexes are untouched bit for bit
+    untouched = np.setdiff1d(np.arange(w.V), rows)
+    assert np.array_equal(out["dE"][untouched].view(np.uint32), base[untouched].view(np.uint32))
+    # every touched row whose oracle gradient is non-zero changed
+    changed = np.flatnonzero(np.any(out["dE"] != base, axis=1))
+    ref_nonzero = rows[np.any(ref.dE[rows] != 0, axis=1)]
+    assert np.array_equal(np.intersect1d(changed, ref_nonzero), ref_nonzero)
+    assert np.all(np.isin(changed, rows))
+    errs = dict(loss=e_loss, lse=e_lse, dH=e_dH, dE=e_dE)
+    print(w.name, {k: f"{v:.2e}" for k, v in errs.items()})
+    assert e_loss <= tol and e_lse <= tol, errs
+    assert e_dH <= (tol if dH_tol is None else dH_tol) and e_dE <= tol, errs
+    return errs
+
+
+def _run(w, **kw):
+    from hip_harness import run_hip
+
+    return run_hip(w, **kw)
+
+
+def test_c1_tiny_fp32_shared_full_size():
+    w = config(1, g_kind="random")
+    assert ((w.neg[None, :] == w.tgt[:, None]) & (w.mask[:, None] != 0)).sum() > 0  # the collision path is exercised
+    check_against_oracle(w, _run(w), TOL_F32)
+
+
+@pytest.mark.parametrize("idx,scale", [(2, 0.02), (3, 0.02), (4, 0.03), (5, 0.004)])
+def test_reduced_configs_gather_path(idx, scale):
+    import paper_2509_09682_amd as P
+
+    w = config(idx, scale=scale, g_kind="random")
+    out = _run(w, algo=P.CCE_ALGO_GATHER)
+    # the gather path computes in fp32 from the exact bf16 inputs: hold it to a much tighter bar than the bf16 target
+    check_against_oracle(w, out, 2e-5)
+
+
+@pytest.mark.parametrize("d", [8, 24, 72, 320, 512])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_hidden_sizes_and_ragged_tail(d, dtype):
+    w = make_workload(f"ragged_d{d}_{dtype}", 1, 37, d, 301, 19, dtype, NEG_PER_POSITION, 99 + d, pad="bernoulli",
+                      pad_p=0.2, g_kind="random", e_sigma=0.3)
+    check_against_oracle(w, _run(w), 2e-5)
+
+
+def test_edge_cases_k0_single_position_all_masked_no_mask_no_g():
+    import paper_2509_09682_amd as P
+
+    w = make_workload("k0", 1, 9, 16, 50, 0, "f32", NEG_SHARED, 7, g_kind="random")
+    out = _run(w)
+    assert np.all(out["loss"] == 0)
+    check_against_oracle(w, out, TOL_F32)
+
+    w = make_workload("n1", 1, 1, 64, 50, 5, "bf16", NEG_SHARED, 8)
+    check_against_oracle(w, _run(w), 2e-5)
+
+    w = make_workload("all_masked", 2, 8, 32, 40, 6, "f32", NEG_PER_POSITION, 9)
+    w.mask[:] = 0
+    w.tgt[:] = -5            # never read
+    w.neg[:] = 1 << 30
+    out = _run(w)
+    assert np.all(out["loss"] == 0) and np.all(out["dH"] == 0) and np.all(out["dE"] == 0)
+
+    w = make_workload("nomask_nog", 2, 13, 64, 200, 17, "bf16", NEG_SHARED, 10)
+    out = _run(w, g=None, use_mask=False)
+    w.mask[:] = 1
+    check_against_oracle(w, out, 2e-5, g=None)
+
+    w = make_workload("dup_collide", 2, 16, 32, 12, 30, "f32", NEG_PER_POSITION, 11, g_kind="random", e_sigma=0.5)
+    for collide in (0, 1):   # V=12 < K: duplicates and collisions everywhere
+        w.mask_collisions = collide
+        check_against_oracle(w, _run(w), TOL_F32)
+
+    # FULL mode in fp32
+    w = make_workload("full_f32", 1, 21, 40, 333, 0, "f32", NEG_FULL, 12, g_kind="random", e_sigma=0.2)
+    check_against_oracle(w, _run(w), TOL_F32)
+    assert P.CCE_OK == 0
+
+
+def test_dE_is_accumulated_into_and_dH_bf16_output():
+    import paper_2509_09682_amd as P
+
+    w = make_workload("accum", 2, 25, 64, 500, 33, "bf16", NEG_SHARED, 21, g_kind="random", pad="right", pad_len_lo=10)
+    init = np.random.default_rng(1).standard_normal((w.V, w.d)).astype(np.float32)
+    out = _run(w, dE_init=init.copy())
+    # the oracle gradient is small next to the N(0,1) initial content, so compare the difference loosely
+    check_against_oracle(w, out, 1e-3, dE_init=init, dH_tol=2e-5)
+    out = _run(w, dH_dtype=P.CCE_BF16)
+    check_against_oracle(w, out, 2e-5, dH_tol=2 ** -8)   # dH rounded to bf16: half an ulp = 2^-9 relative
+
+
+def test_index_validation_skips_bad_ids_and_reports():
+    import paper_2509_09682_amd as P
+
+    w = make_workload("validate", 2, 10, 32, 100, 8, "f32", NEG_PER_POSITION, 31, g_kind="random")
+    clean = _run(w, validate=1)
+    assert clean["status"] == P.CCE_OK
+    bad = make_workload("validate", 2, 10, 32, 100, 8, "f32", NEG_PER_POSITION, 31, g_kind="random")
+    bad.neg[3, 2] = 100            # == V: out of range
+    bad.neg[5, 0] = -1
+    bad.tgt[7] = 12345
+    out = _run(bad, validate=1)
+    assert out["status"] == P.CCE_ERR_INDEX
+    # the oracle on the sanitised problem: bad negatives dropped = replaced by a collision, bad target = masked
+    ref = make_workload("validate", 2, 10, 32, 100, 8, "f32", NEG_PER_POSITION, 31, g_kind="random")
+    ref.neg[3, 2] = ref.tgt[3]
+    ref.neg[5, 0] = ref.tgt[5]
+    ref.mask[7] = 0
+    check_against_oracle(ref, out, TOL_F32)
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_full_size_configs_against_full_oracle(idx):
+    """The benchmark shapes, every output element held against the oracle (the oracle finishes these in seconds)."""
+    w = config(idx)
+    out = _run(w)
+    tol = TOL_BF16
+    errs = check_against_oracle(w, out, tol)
+    # zero column sum of dE: sum_v dE[v,:] = sum_i g_i (sum_j p_ij - 1) h_i = 0
+    scale = np.abs(out["dE"]).sum(0).max()
+    assert np.abs(out["dE"].astype(np.float64).sum(0)).max() <= 1e-3 * scale, errs

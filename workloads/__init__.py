@@ -7,6 +7,10 @@ oracle's tests and the HIP path's tests import.
 """
 from .generators import (  # noqa: F401
     Workload,
+    NEG_SHARED,
+    NEG_PER_POSITION,
+    NEG_FULL,
+    BASE_SEED,
     CONFIG_NAMES,
     make_workload,
     config,
