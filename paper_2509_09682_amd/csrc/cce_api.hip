@@ -7,7 +7,59 @@
 namespace cce {
 namespace {
 
-constexpr size_t kHeaderBytes = 256;  // status word + padding; keeps what follows 256-byte aligned
+constexpr size_t kHeaderBytes = 256;  // status word, compaction counters; keeps what follows 256-byte aligned
+
+size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
+
+// The matrix-core path runs bf16 shared-negative and full-catalogue descriptors with a supported hidden size.
+bool tile_eligible(const cce_desc *d)
+{
+    if (d->in_dtype != CCE_BF16 || d->neg_mode == CCE_NEG_PER_POSITION || !tile_supports_d(d->d)) return false;
+    const int64_t n_cols = (d->neg_mode == CCE_NEG_FULL) ? d->V : d->K;
+    return n_cols >= 1;
+}
+bool use_tile(const cce_desc *d) { return d->algo != CCE_ALGO_GATHER && tile_eligible(d); }
+
+// Workspace layout of the matrix-core path.  Split factors depend on the descriptor only, so that the size query and
+// the launches agree.
+struct Layout {
+    size_t idx, cnt, coef, part_m, part_s, part_dH, total;
+    int splits_x;   // forward / dH passes: candidate range split over this many blocks per position block
+    int splits_de;  // dE pass: position range split
+};
+
+Layout make_layout(const cce_desc *d)
+{
+    Layout L{};
+    const int64_t N = d->N;
+    const int64_t n_cols = (d->neg_mode == CCE_NEG_FULL) ? d->V : d->K;
+    const int by = (d->d <= 128) ? 64 : 32;
+    const int64_t xblocks = (N + 127) / 128;
+    int sx = 1;
+    if (xblocks > 0 && xblocks < 384) sx = (int)((768 + xblocks - 1) / xblocks);
+    const int64_t col_tiles = (n_cols + by - 1) / by;
+    if (sx > 16) sx = 16;
+    if (sx > col_tiles / 4) sx = (int)(col_tiles / 4);
+    if (sx < 1) sx = 1;
+    L.splits_x = sx;
+    const int64_t cblocks = (n_cols + 127) / 128;
+    int sd = 1;
+    if (cblocks > 0 && cblocks < 512) sd = (int)((512 + cblocks - 1) / cblocks);
+    const int64_t pos_tiles = (N + by - 1) / by;
+    if (sd > pos_tiles / 4) sd = (int)(pos_tiles / 4);
+    if (sd < 1) sd = 1;
+    L.splits_de = sd;
+
+    size_t off = kHeaderBytes;
+    L.idx = off;      off += align256((size_t)N * 4);
+    L.cnt = off;      off += align256((size_t)N * 4);
+    L.coef = off;     off += align256((size_t)N * 4);
+    L.part_m = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
+    L.part_s = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
+    L.part_dH = off;  off += (sx > 1) ? align256((size_t)sx * N * d->d * 4) : 0;
+    L.total = off;
+    return L;
+}
 
 __global__ void fill_zero_kernel(int32_t *dst, size_t words)
 {
@@ -27,7 +79,7 @@ cce_status check_desc(const cce_desc *d)
     if (d->dH_dtype != CCE_F32 && d->dH_dtype != CCE_BF16) return CCE_ERR_DTYPE;
     if (d->dH_dtype == CCE_BF16 && d->in_dtype != CCE_BF16) return CCE_ERR_DTYPE;
     if (d->algo != CCE_ALGO_AUTO && d->algo != CCE_ALGO_GATHER && d->algo != CCE_ALGO_TILE) return CCE_ERR_UNSUPPORTED;
-    if (d->algo == CCE_ALGO_TILE) return CCE_ERR_UNSUPPORTED;  // matrix-core path not built yet
+    if (d->algo == CCE_ALGO_TILE && !tile_eligible(d)) return CCE_ERR_UNSUPPORTED;
     return CCE_OK;
 }
 
@@ -64,6 +116,58 @@ Params make_params(const cce_desc *d, const void *H, const void *E, const int32_
     return p;
 }
 
+TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const void *E, const int32_t *tgt,
+                        const int32_t *neg, const uint8_t *mask, void *workspace)
+{
+    char *ws = static_cast<char *>(workspace);
+    int32_t *header = static_cast<int32_t *>(workspace);
+    const bool compact = (mask != nullptr) || d->validate_indices;
+    const bool shared = (d->neg_mode == CCE_NEG_SHARED);
+    TileArgs a{};
+    a.H = static_cast<const uint16_t *>(H);
+    a.E = static_cast<const uint16_t *>(E);
+    a.tgt = tgt;
+    a.neg = shared ? neg : nullptr;
+    a.idx = compact ? reinterpret_cast<const int32_t *>(ws + L.idx) : nullptr;
+    a.n_valid_ptr = compact ? header + kHdrNValid : nullptr;
+    a.cnt = (shared && d->mask_target_collisions) ? reinterpret_cast<const int32_t *>(ws + L.cnt) : nullptr;
+    a.coef = reinterpret_cast<float *>(ws + L.coef);
+    a.part_m = reinterpret_cast<float *>(ws + L.part_m);
+    a.part_s = reinterpret_cast<float *>(ws + L.part_s);
+    a.part_dH = reinterpret_cast<float *>(ws + L.part_dH);
+    a.N = d->N;
+    a.V = d->V;
+    a.n_cols = shared ? d->K : d->V;
+    a.d = d->d;
+    a.splits = L.splits_x;
+    a.pos_weight_mode = shared ? 0 : 2;
+    a.dH_bf16 = (d->dH_dtype == CCE_BF16) ? 1 : 0;
+    a.validate = d->validate_indices ? 1 : 0;
+    return a;
+}
+
+PrepArgs make_prep_args(const cce_desc *d, const Layout &L, const int32_t *tgt, const int32_t *neg,
+                        const uint8_t *mask, void *workspace)
+{
+    char *ws = static_cast<char *>(workspace);
+    const bool compact = (mask != nullptr) || d->validate_indices;
+    const bool shared = (d->neg_mode == CCE_NEG_SHARED);
+    PrepArgs p{};
+    p.tgt = tgt;
+    p.neg = shared ? neg : nullptr;
+    p.mask = mask;
+    p.header = static_cast<int32_t *>(workspace);
+    p.idx = compact ? reinterpret_cast<int32_t *>(ws + L.idx) : nullptr;
+    p.cnt = (shared && d->mask_target_collisions) ? reinterpret_cast<int32_t *>(ws + L.cnt) : nullptr;
+    p.N = d->N;
+    p.V = d->V;
+    p.d = d->d;
+    p.K = shared ? d->K : 0;
+    p.validate = d->validate_indices ? 1 : 0;
+    p.dH_bf16 = (d->dH_dtype == CCE_BF16) ? 1 : 0;
+    return p;
+}
+
 }  // namespace
 
 hipError_t launch_fill_zero(int32_t *dst, size_t words, hipStream_t stream)
@@ -80,6 +184,7 @@ extern "C" {
 size_t cce_neg_workspace_bytes(const cce_desc *desc)
 {
     if (cce::check_desc(desc) != CCE_OK) return 0;
+    if (cce::use_tile(desc)) return cce::make_layout(desc).total;
     return cce::kHeaderBytes;
 }
 
@@ -99,10 +204,24 @@ cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, c
     const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
     if (st != CCE_OK) return st;
     if (!loss || !lse) return CCE_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (cce::use_tile(desc)) {
+        const cce::Layout L = cce::make_layout(desc);
+        cce::PrepArgs pa = cce::make_prep_args(desc, L, tgt, neg, mask, workspace);
+        pa.loss = loss;
+        pa.lse = lse;
+        if (pa.idx || pa.cnt) {
+            if (cce::launch_prep(pa, stream) != hipSuccess) return CCE_ERR_HIP;
+        }
+        cce::TileArgs a = cce::make_tile_args(desc, L, H, E, tgt, neg, mask, workspace);
+        a.loss = loss;
+        a.lse = lse;
+        return cce::launch_tile(cce::TILE_PASS_FWD, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+    }
     cce::Params p = cce::make_params(desc, H, E, tgt, neg, mask, workspace);
     p.loss = loss;
     p.lse = lse;
-    const hipError_t e = cce::launch_gather(false, desc->in_dtype == CCE_BF16, p, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = cce::launch_gather(false, desc->in_dtype == CCE_BF16, p, stream);
     return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 
@@ -113,12 +232,30 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
     if (st != CCE_OK) return st;
     if (!lse || !dH || !dE) return CCE_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (cce::use_tile(desc)) {
+        const cce::Layout L = cce::make_layout(desc);
+        cce::PrepArgs pa = cce::make_prep_args(desc, L, tgt, neg, mask, workspace);
+        pa.dH = dH;
+        if (pa.idx || pa.cnt) {
+            if (cce::launch_prep(pa, stream) != hipSuccess) return CCE_ERR_HIP;
+        }
+        cce::TileArgs a = cce::make_tile_args(desc, L, H, E, tgt, neg, mask, workspace);
+        a.lse_in = lse;
+        a.g = grad_loss;
+        a.dH = dH;
+        a.dE = dE;
+        if (cce::launch_tile(cce::TILE_PASS_DH, a, stream) != hipSuccess) return CCE_ERR_HIP;
+        if (cce::launch_tile(cce::TILE_PASS_POS, a, stream) != hipSuccess) return CCE_ERR_HIP;
+        a.splits = L.splits_de;
+        return cce::launch_tile(cce::TILE_PASS_DE, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+    }
     cce::Params p = cce::make_params(desc, H, E, tgt, neg, mask, workspace);
     p.lse_in = lse;
     p.g = grad_loss;
     p.dH = dH;
     p.dE = dE;
-    const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, static_cast<hipStream_t>(hip_stream));
+    const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream);
     return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 

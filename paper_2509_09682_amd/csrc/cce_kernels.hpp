@@ -1,4 +1,4 @@
-// Host-side launch entry points of the kernel families (internal to the library).
+// Host-side launch entry points of the kernel families and their argument blocks (internal to the library).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -6,8 +6,51 @@
 
 namespace cce {
 
-// One wavefront per position, rows gathered one by one; any mode, fp32 or bf16 inputs.
+// 32-bit words of the workspace header.
+enum { kHdrStatus = 0, kHdrTotal = 1, kHdrDone = 2, kHdrNValid = 3 };
+
+// ---- row-gather family: one wavefront per position; any mode, fp32 or bf16 inputs
 hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream);
+
+// ---- matrix-core family: bf16 inputs, shared negatives or full catalogue
+struct PrepArgs {
+    const int32_t *tgt;
+    const int32_t *neg;    // shared negatives [K] or nullptr
+    const uint8_t *mask;   // nullable
+    int32_t *header;       // workspace header words
+    int32_t *idx;          // out: compacted valid positions (nullptr: no compaction wanted)
+    int32_t *cnt;          // out: multiplicity of the target among the negatives (nullptr: not wanted)
+    float *loss, *lse;     // forward: zeroed for padded positions (nullable)
+    void *dH;              // backward: rows of padded positions zeroed (nullable)
+    int64_t N, V;
+    int32_t d, K, validate, dH_bf16;
+};
+
+struct TileArgs {
+    const uint16_t *H;
+    const uint16_t *E;
+    const int32_t *tgt;
+    const int32_t *neg;          // candidate column -> item row; nullptr = identity (full catalogue)
+    const int32_t *idx;          // compacted position -> position row; nullptr = identity
+    const int32_t *n_valid_ptr;  // device count of valid positions; nullptr = N
+    const int32_t *cnt;          // target multiplicity per position; nullptr = 0
+    const float *lse_in;
+    const float *g;
+    float *loss, *lse;
+    void *dH;
+    float *dE;
+    float *coef;                 // [N] coefficient of the correct item, written by the dH pass, read by the scatter
+    float *part_m, *part_s;      // [splits, N] partial max / sum of split forward runs
+    float *part_dH;              // [splits, N, d] partial dH of split runs
+    int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode
+    int32_t d, splits, pos_weight_mode, dH_bf16, validate;
+};
+
+enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2, TILE_PASS_POS = 3 };
+
+bool tile_supports_d(int d);
+hipError_t launch_prep(const PrepArgs &p, hipStream_t stream);
+hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 
 // Clears `words` 32-bit words at dst with a fill kernel (no memset node).
 hipError_t launch_fill_zero(int32_t *dst, size_t words, hipStream_t stream);

@@ -64,6 +64,58 @@ def test_reduced_configs_gather_path(idx, scale):
     check_against_oracle(w, out, 2e-5)
 
 
+@pytest.mark.parametrize("idx,scale", [(2, 0.03), (4, 0.05), (5, 0.006)])
+def test_reduced_configs_tile_path(idx, scale):
+    import paper_2509_09682_amd as P
+
+    w = config(idx, scale=scale, g_kind="random")
+    out = _run(w, algo=P.CCE_ALGO_TILE)
+    check_against_oracle(w, out, TOL_BF16)
+
+
+@pytest.mark.parametrize("d", [64, 128, 256])
+@pytest.mark.parametrize("mode", [NEG_SHARED, NEG_FULL])
+def test_tile_path_ragged_shapes_collisions_and_duplicates(d, mode):
+    """Sizes that are no multiple of any tile edge, a catalogue so small that negatives repeat and hit targets."""
+    import paper_2509_09682_amd as P
+
+    K = 0 if mode == NEG_FULL else 203
+    V = 1003 if mode == NEG_FULL else 157
+    w = make_workload(f"tile_ragged_d{d}_m{mode}", 7, 61, d, V, K, "bf16", mode, 500 + d + mode, pad="right",
+                      pad_len_lo=20, g_kind="random", e_sigma=0.1, tgt_dist="zipf")
+    if mode == NEG_SHARED:
+        dup = (w.neg[None, :] == w.tgt[:, None]).sum(1)
+        assert dup.max() >= 2          # some target appears several times among the negatives
+    for collide in ((0, 1) if mode == NEG_SHARED else (1,)):
+        w.mask_collisions = collide
+        out = _run(w, algo=P.CCE_ALGO_TILE)
+        check_against_oracle(w, out, TOL_BF16)
+    out = _run(w, algo=P.CCE_ALGO_TILE, dH_dtype=P.CCE_BF16, use_mask=False, g=None)
+    w.mask[:] = 1
+    check_against_oracle(w, out, TOL_BF16, g=None)
+
+
+def test_tile_path_many_positions_splits_the_dE_pass():
+    import paper_2509_09682_amd as P
+
+    w = make_workload("tile_split_de", 40, 77, 64, 5000, 130, "bf16", NEG_SHARED, 777, pad="bernoulli", pad_p=0.3,
+                      g_kind="random", e_sigma=0.05, tgt_dist="zipf", zipf_s=1.2)
+    out = _run(w, algo=P.CCE_ALGO_TILE)
+    check_against_oracle(w, out, TOL_BF16)
+
+
+def test_tile_path_index_validation_reports_and_stays_in_bounds():
+    import paper_2509_09682_amd as P
+
+    w = make_workload("tile_validate", 3, 50, 64, 300, 96, "bf16", NEG_SHARED, 41, g_kind="random")
+    assert _run(w, algo=P.CCE_ALGO_TILE, validate=1)["status"] == P.CCE_OK
+    w.neg[5] = 300
+    w.neg[17] = -3
+    w.tgt[11] = 1 << 20
+    out = _run(w, algo=P.CCE_ALGO_TILE, validate=1)
+    assert out["status"] == P.CCE_ERR_INDEX   # outputs of a flagged call are unspecified; it must only not fault
+
+
 @pytest.mark.parametrize("d", [8, 24, 72, 320, 512])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_hidden_sizes_and_ragged_tail(d, dtype):
@@ -81,7 +133,8 @@ def test_edge_cases_k0_single_position_all_masked_no_mask_no_g():
     check_against_oracle(w, out, TOL_F32)
 
     w = make_workload("n1", 1, 1, 64, 50, 5, "bf16", NEG_SHARED, 8)
-    check_against_oracle(w, _run(w), 2e-5)
+    check_against_oracle(w, _run(w, algo=P.CCE_ALGO_GATHER), 2e-5)
+    check_against_oracle(w, _run(w, algo=P.CCE_ALGO_TILE), TOL_BF16)
 
     w = make_workload("all_masked", 2, 8, 32, 40, 6, "f32", NEG_PER_POSITION, 9)
     w.mask[:] = 0
@@ -91,9 +144,9 @@ def test_edge_cases_k0_single_position_all_masked_no_mask_no_g():
     assert np.all(out["loss"] == 0) and np.all(out["dH"] == 0) and np.all(out["dE"] == 0)
 
     w = make_workload("nomask_nog", 2, 13, 64, 200, 17, "bf16", NEG_SHARED, 10)
-    out = _run(w, g=None, use_mask=False)
     w.mask[:] = 1
-    check_against_oracle(w, out, 2e-5, g=None)
+    check_against_oracle(w, _run(w, g=None, use_mask=False, algo=P.CCE_ALGO_GATHER), 2e-5, g=None)
+    check_against_oracle(w, _run(w, g=None, use_mask=False), TOL_BF16, g=None)
 
     w = make_workload("dup_collide", 2, 16, 32, 12, 30, "f32", NEG_PER_POSITION, 11, g_kind="random", e_sigma=0.5)
     for collide in (0, 1):   # V=12 < K: duplicates and collisions everywhere
@@ -111,11 +164,12 @@ def test_dE_is_accumulated_into_and_dH_bf16_output():
 
     w = make_workload("accum", 2, 25, 64, 500, 33, "bf16", NEG_SHARED, 21, g_kind="random", pad="right", pad_len_lo=10)
     init = np.random.default_rng(1).standard_normal((w.V, w.d)).astype(np.float32)
-    out = _run(w, dE_init=init.copy())
-    # the oracle gradient is small next to the N(0,1) initial content, so compare the difference loosely
-    check_against_oracle(w, out, 1e-3, dE_init=init, dH_tol=2e-5)
-    out = _run(w, dH_dtype=P.CCE_BF16)
-    check_against_oracle(w, out, 2e-5, dH_tol=2 ** -8)   # dH rounded to bf16: half an ulp = 2^-9 relative
+    for algo, tol in ((P.CCE_ALGO_GATHER, 2e-5), (P.CCE_ALGO_TILE, TOL_BF16)):
+        out = _run(w, dE_init=init.copy(), algo=algo)
+        # the gradient is small next to the N(0,1) initial content: the difference carries the rounding of the sum
+        check_against_oracle(w, out, max(tol, 1e-3), dE_init=init, dH_tol=tol)
+        out = _run(w, dH_dtype=P.CCE_BF16, algo=algo)
+        check_against_oracle(w, out, tol, dH_tol=max(tol, 2 ** -8))   # dH rounded to bf16: half an ulp = 2^-9
 
 
 def test_index_validation_skips_bad_ids_and_reports():
