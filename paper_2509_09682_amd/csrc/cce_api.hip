@@ -33,20 +33,22 @@ Layout make_layout(const cce_desc *d)
     Layout L{};
     const int64_t N = d->N;
     const int64_t n_cols = (d->neg_mode == CCE_NEG_FULL) ? d->V : d->K;
-    const int by = (d->d <= 128) ? 64 : 32;
+    const int by = 8192 / d->d;  // streamed rows per tile, as in the kernels
+    // Upper bounds of the split factors (the launcher picks the factor that fills the chip best, up to these).
+    // Splitting only pays when there are few blocks of stationary rows, which bounds splits * rows, hence the
+    // partial buffers, by a constant.
     const int64_t xblocks = (N + 127) / 128;
-    int sx = 1;
-    if (xblocks > 0 && xblocks < 384) sx = (int)((768 + xblocks - 1) / xblocks);
+    int sx = (xblocks > 0) ? (int)(2048 / xblocks) : 1;
     const int64_t col_tiles = (n_cols + by - 1) / by;
     if (sx > 16) sx = 16;
-    if (sx > col_tiles / 4) sx = (int)(col_tiles / 4);
+    if (sx > col_tiles / 2) sx = (int)(col_tiles / 2);
     if (sx < 1) sx = 1;
     L.splits_x = sx;
     const int64_t cblocks = (n_cols + 127) / 128;
-    int sd = 1;
-    if (cblocks > 0 && cblocks < 512) sd = (int)((512 + cblocks - 1) / cblocks);
+    int sd = (cblocks > 0) ? (int)(2048 / cblocks) : 1;
     const int64_t pos_tiles = (N + by - 1) / by;
-    if (sd > pos_tiles / 4) sd = (int)(pos_tiles / 4);
+    if (sd > 128) sd = 128;
+    if (sd > pos_tiles / 2) sd = (int)(pos_tiles / 2);
     if (sd < 1) sd = 1;
     L.splits_de = sd;
 
@@ -246,7 +248,6 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
         a.dH = dH;
         a.dE = dE;
         if (cce::launch_tile(cce::TILE_PASS_DH, a, stream) != hipSuccess) return CCE_ERR_HIP;
-        if (cce::launch_tile(cce::TILE_PASS_POS, a, stream) != hipSuccess) return CCE_ERR_HIP;
         a.splits = L.splits_de;
         return cce::launch_tile(cce::TILE_PASS_DE, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
     }

@@ -43,10 +43,11 @@ struct TileArgs {
     float *part_m, *part_s;      // [splits, N] partial max / sum of split forward runs
     float *part_dH;              // [splits, N, d] partial dH of split runs
     int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode
-    int32_t d, splits, pos_weight_mode, dH_bf16, validate;
+    int64_t de_blocks;           // dE launch: blocks [0, de_blocks) run the dE pass, the rest scatter the correct items
+    int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
 };
 
-enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2, TILE_PASS_POS = 3 };
+enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items
 
 bool tile_supports_d(int d);
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream);

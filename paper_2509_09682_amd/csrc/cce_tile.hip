@@ -32,10 +32,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kThreads = 256;
-constexpr int kXPerWave = 32;
-constexpr int kXPerBlock = 128;
-constexpr int kPad = 8;  // bf16 elements of padding per LDS row
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DE = 2 };
 
@@ -86,19 +82,133 @@ __device__ __forceinline__ float half_row_dot(const uint4 (&xr)[D / 16], const u
     return s;
 }
 
-template <int D, int MODE, int BY>
-__global__ __launch_bounds__(kThreads, 2) void tile_kernel(TileArgs a)
-{
-    constexpr int KK = D / 16;           // k-steps of the score product
-    constexpr int MB = D / 32;           // 32-row output blocks of the second product
-    constexpr int ROW = D + kPad;        // LDS row pitch in elements
-    constexpr int CPR = D / 8;           // 16-byte chunks per row
-    constexpr int CH = BY * CPR / kThreads;  // chunks staged per thread and tile
-    static_assert(BY * CPR % kThreads == 0, "tile must split evenly over the threads");
+// XOR pattern of the 16-byte chunk position inside an unpadded LDS row.  It takes 8 different values on 8 consecutive
+// rows (conflict-free 128-bit operand reads, one row per lane) and its upper two bits differ on 4 consecutive rows
+// (conflict-free transpose reads, which fetch 32 bytes from each of 4 rows).
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
-    __shared__ __attribute__((aligned(16))) uint16_t ytile[2][BY * ROW];
-    __shared__ float yconst[2][BY];
-    __shared__ uint32_t ysign[2][BY];
+typedef const void __attribute__((address_space(1))) *global_cptr;
+typedef void __attribute__((address_space(3))) *lds_ptr;
+typedef s16x4 __attribute__((address_space(3))) *lds_v4;
+
+// dE of the correct items: dE[tgt_i] += coef_i * H_i.  Targets follow a power law, so plain atomics would serialise
+// on a few hot rows (an atomic on one address completes every ~25 ns).  A block sorts 256 (target, position) pairs in
+// LDS; every wavefront then walks 64 consecutive sorted pairs with lane = column, sums runs of equal targets in
+// registers and issues one row of atomics per run.  These blocks ride in the launch of the dE pass, after its own
+// blocks, so that their latency (sort, dependent gathers) hides under the matrix work.
+constexpr int kPosChunk = 256;
+constexpr int kPosBatch = 16;  // rows in flight per wavefront
+
+template <int D>
+__device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chunk, uint64_t *keys)
+{
+    constexpr int CPL = D / 64;  // columns per lane
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
+    const int64_t base = chunk * kPosChunk;
+    if (base >= n_pos) return;
+    {
+        uint64_t key = ~0ull;  // padding sorts last
+        if (base + tid < n_pos) {
+            const int64_t row = pos_row(a, base + tid);
+            key = ((uint64_t)(uint32_t)a.tgt[row] << 32) | (uint32_t)row;
+        }
+        keys[tid] = key;
+    }
+    __syncthreads();
+    for (int k = 2; k <= kPosChunk; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const int partner = tid ^ j;
+            if (partner > tid) {
+                const uint64_t ka = keys[tid], kb = keys[partner];
+                const bool up = ((tid & k) == 0);
+                if ((ka > kb) == up) {
+                    keys[tid] = kb;
+                    keys[partner] = ka;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    float accv[CPL];
+#pragma unroll
+    for (int t = 0; t < CPL; ++t) accv[t] = 0.f;
+    uint32_t cur = 0xffffffffu;
+    auto flush = [&]() {
+        if (cur != 0xffffffffu) {
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) {
+                unsafeAtomicAdd(a.dE + (int64_t)cur * D + lane * CPL + t, accv[t]);
+                accv[t] = 0.f;
+            }
+        }
+    };
+    // lane l holds pair l of the wavefront's 64 sorted pairs and its coefficient; the walk broadcasts them lane by lane
+    const uint64_t my_key = keys[wave * 64 + lane];
+    const uint32_t my_id = (uint32_t)(my_key >> 32), my_row = (uint32_t)my_key;
+    const float my_cf = (my_id != 0xffffffffu) ? a.coef[my_row] : 0.f;
+    for (int b = 0; b < 64; b += kPosBatch) {
+        uint32_t id[kPosBatch];
+        float hv[kPosBatch][CPL];
+#pragma unroll
+        for (int u = 0; u < kPosBatch; ++u) {
+            id[u] = __builtin_amdgcn_readlane(my_id, b + u);
+            const uint32_t row = __builtin_amdgcn_readlane(my_row, b + u);
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) hv[u][t] = 0.f;
+            if (id[u] != 0xffffffffu) {
+#pragma unroll
+                for (int t = 0; t < CPL; ++t) hv[u][t] = load1(a.H + (int64_t)row * D + lane * CPL + t);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kPosBatch; ++u) {
+            if (id[u] != cur) {
+                flush();
+                cur = id[u];
+            }
+            const float cf = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_cf), b + u));
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) accv[t] = fmaf(cf, hv[u][t], accv[t]);
+        }
+    }
+    flush();
+}
+
+// Largest of three floats in one instruction; the operands are never NaN here, so no canonicalisation is wanted.
+__device__ __forceinline__ float max3(float x, float y, float z)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z));
+    return r;
+}
+
+// D: hidden size.  BY: streamed rows per LDS tile.  NW: wavefronts per block.  XG: groups of 32 stationary rows per
+// wavefront (XG = 2 reads every streamed operand from LDS once for two matrix instructions).  MINB: blocks per
+// compute unit the register budget is sized for.
+template <int D, int MODE, int BY, int NW, int XG, int MINB, bool DUAL>
+__global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
+{
+    constexpr int KK = D / 16;             // k-steps of the score product
+    constexpr int MB = D / 32;             // 32-row output blocks of the second product
+    constexpr int CPR = D / 8;             // 16-byte chunks per row
+    constexpr int XPB = NW * XG * 32;      // stationary rows per block
+    constexpr int TILE = BY * D;           // elements per LDS tile
+    constexpr int LOADS = BY * CPR / 64;   // 1-KiB direct-to-LDS load instructions per tile
+    static_assert(LOADS % NW == 0, "tile loads must split evenly over the wavefronts");
+    constexpr int LPW = LOADS / NW;
+    static_assert(NW % 2 == 0 && TILE * 2 >= (NW / 2) * 32 * 33 * 4, "tile buffers too small for the dE transpose");
+
+    // Two tile buffers.  As separate arrays (DUAL, main loop unrolled twice) the compiler knows that operand reads of
+    // one buffer cannot touch the other and does not wait for the loads in flight into it; the single-array form
+    // keeps one copy of the loop body where registers are short, and leans on the second block of the compute unit.
+    __shared__ __attribute__((aligned(1024))) uint16_t tileA[DUAL ? TILE : 2 * TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t tileB_[DUAL ? TILE : 8];
+    uint16_t *const tileB = DUAL ? tileB_ : tileA + TILE;
+    __shared__ __attribute__((aligned(16))) float ycA[BY], ycB[BY];
+    __shared__ __attribute__((aligned(16))) uint32_t ysA[BY], ysB[BY];
+    __shared__ int64_t xrow_s[XPB];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -106,266 +216,356 @@ __global__ __launch_bounds__(kThreads, 2) void tile_kernel(TileArgs a)
     const int lo = lane & 31;
     const int hi = lane >> 5;
 
+    if (MODE == MODE_DE && (int64_t)blockIdx.x >= a.de_blocks) {  // trailing blocks: scatter of the correct items
+        static_assert(NW * 64 == kPosChunk, "the scatter role expects 256 threads");
+        pos_scatter_block<D>(a, (int64_t)blockIdx.x - a.de_blocks, reinterpret_cast<uint64_t *>(tileA));
+        return;
+    }
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t n_x = (MODE == MODE_DE) ? a.n_cols : n_pos;
     const int64_t n_y = (MODE == MODE_DE) ? n_pos : a.n_cols;
     const int split = blockIdx.x % a.splits;
     const int64_t xb = blockIdx.x / a.splits;
-    if (xb * kXPerBlock >= n_x) return;  // whole block past the end (the grid is sized for the unmasked N)
+    if (xb * XPB >= n_x) return;  // whole block past the end (the grid is sized for the unmasked N)
 
     const uint16_t *Xbase = (MODE == MODE_DE) ? a.E : a.H;
     const uint16_t *Ybase = (MODE == MODE_DE) ? a.H : a.E;
 
     // ---- stationary rows -> registers in B-operand layout: lane (lo, hi) holds X[x][kk*16 + hi*8 .. +8]
-    const int64_t x = xb * kXPerBlock + wave * kXPerWave + lo;
-    const bool x_ok = x < n_x;
-    const int64_t xrow = (MODE == MODE_DE) ? item_row(a, x_ok ? x : 0) : pos_row(a, x_ok ? x : 0);
-    uint4 xr[KK];
-    {
-        const uint16_t *xp = Xbase + xrow * D;
+    int64_t xrow[XG];
+    bool x_ok[XG];
+    uint4 xr[XG][KK];
+    float cx[XG];  // DH: -lse * log2(e) of the lane's position
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) xr[kk] = *reinterpret_cast<const uint4 *>(xp + kk * 16 + hi * 8);
+    for (int g = 0; g < XG; ++g) {
+        const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+        x_ok[g] = x < n_x;
+        xrow[g] = (MODE == MODE_DE) ? item_row(a, x_ok[g] ? x : 0) : pos_row(a, x_ok[g] ? x : 0);
+        const uint16_t *xp = Xbase + xrow[g] * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) xr[g][kk] = *reinterpret_cast<const uint4 *>(xp + kk * 16 + hi * 8);
+        cx[g] = 0.f;
+        if (MODE == MODE_DH) cx[g] = -a.lse_in[xrow[g]] * kLog2e;
     }
-    float cx = 0.f;  // DH: -lse * log2(e) of the lane's position
-    if (MODE == MODE_DH) cx = -a.lse_in[xrow] * kLog2e;
 
     // ---- range of streamed tiles of this split
     const int64_t n_tiles = (n_y + BY - 1) / BY;
     const int64_t t_begin = n_tiles * split / a.splits;
     const int64_t t_end = n_tiles * (split + 1) / a.splits;
 
-    f32x16 acc[MODE == MODE_FWD ? 1 : MB];
+    f32x16 acc[XG][MODE == MODE_FWD ? 1 : MB];
     if (MODE != MODE_FWD) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int g = 0; g < XG; ++g)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[mb][q] = 0.f;
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc[g][mb][q] = 0.f;
     }
-    float run_m = -INFINITY, run_s = 0.f;  // FWD: base-2 running max and sum of this lane's half of the candidates
+    float run_m[XG], run_s[XG];  // FWD: base-2 running max and sum of this lane's half of the candidates
+#pragma unroll
+    for (int g = 0; g < XG; ++g) {
+        run_m[g] = -INFINITY;
+        run_s[g] = 0.f;
+    }
 
-    uint4 stage[CH];
+    // ---- streamed tiles: global memory -> LDS without passing through registers.  One instruction moves 1 KiB:
+    //      lane l of the wavefront writes 16 bytes at (wave-uniform base) + 16 l, so the lane that owns LDS slot
+    //      (row r, physical chunk pc) fetches the logical chunk pc ^ swz(r) of that row.
     float stage_c = 0.f;
     uint32_t stage_s = 0;
-    auto load_tile = [&](int64_t t) {
+    // Row numbers of the streamed rows are fetched one tile ahead of the rows themselves, so that the address of a
+    // direct-to-LDS load never waits for an index load issued in the same step.
+    int64_t next_row[LPW];
+    int64_t next_crow = 0;  // DE: position row whose constants thread tid publishes
+    auto fetch_rows = [&](int64_t t) {
         const int64_t y0 = t * BY;
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int c = tid + u * kThreads;
-            const int r = c / CPR, col = c % CPR;
-            const int64_t y = y0 + r;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (y < n_y) {
-                const int64_t row = (MODE == MODE_DE) ? pos_row(a, y) : item_row(a, y);
-                v = *reinterpret_cast<const uint4 *>(Ybase + row * D + col * 8);
-            }
-            stage[u] = v;
+        for (int i = 0; i < LPW; ++i) {
+            const int r = ((wave + i * NW) * 64 + lane) / CPR;
+            int64_t y = y0 + r;
+            if (y >= n_y) y = n_y - 1;  // rows past the end repeat the last row (finite data); they are masked below
+            next_row[i] = (MODE == MODE_DE) ? pos_row(a, y) : item_row(a, y);
         }
         if (MODE == MODE_DE && tid < BY) {
-            const int64_t y = y0 + tid;
+            int64_t y = y0 + tid;
+            if (y >= n_y) y = n_y - 1;
+            next_crow = pos_row(a, y);
+        }
+    };
+    auto issue_tile = [&](int64_t t, uint16_t *dst_tile) {
+        const int64_t y0 = t * BY;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int inst = wave + i * NW;
+            const int L = inst * 64 + lane;
+            const int r = L / CPR, pc = L % CPR;
+            const int c = (pc & ~7) | ((pc & 7) ^ swz(r));
+            const uint16_t *src = Ybase + next_row[i] * D + c * 8;
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst_tile + inst * 512), 16, 0, 0);
+        }
+        if (MODE == MODE_DE && tid < BY) {
             stage_c = -INFINITY;
             stage_s = 0;
-            if (y < n_y) {
-                const int64_t row = pos_row(a, y);
-                const float g = a.g ? a.g[row] : 1.f;
+            if (y0 + tid < n_y) {
+                const float g = a.g ? a.g[next_crow] : 1.f;
                 // g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|)
-                stage_c = -a.lse_in[row] * kLog2e + __builtin_amdgcn_logf(fabsf(g));
+                stage_c = -a.lse_in[next_crow] * kLog2e + __builtin_amdgcn_logf(fabsf(g));
                 stage_s = __float_as_uint(g) & 0x80000000u;
             }
         }
+        if (t + 1 < t_end) fetch_rows(t + 1);
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int c = tid + u * kThreads;
-            const int r = c / CPR, col = c % CPR;
-            *reinterpret_cast<uint4 *>(&ytile[buf][r * ROW + col * 8]) = stage[u];
-        }
+    auto publish_consts = [&](float *yc, uint32_t *ys) {
         if (MODE == MODE_DE && tid < BY) {
-            yconst[buf][tid] = stage_c;
-            ysign[buf][tid] = stage_s;
+            yc[tid] = stage_c;
+            ys[tid] = stage_s;
+        }
+    };
+
+    // per-lane pieces of the swizzled LDS addresses (elements)
+    int a_off[4];  // operand reads of the score product: chunk kk*2 + hi of row lo
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) a_off[k4] = lo * D + (((k4 * 2 + hi) ^ swz(lo)) * 8);
+    const int j16 = lane & 15, ta = j16 >> 2, tb = j16 & 3, cb = (lane >> 4) & 1;
+    int t_off[2];  // transpose reads of the second product: row hi*4 + ta, chunk mb*4 + cb*2 + tb/2
+#pragma unroll
+    for (int m2 = 0; m2 < 2; ++m2)
+        t_off[m2] = (hi * 4 + ta) * D + (((m2 * 4 + cb * 2 + (tb >> 1)) ^ swz(hi * 4 + ta)) * 8) + (tb & 1) * 4;
+
+    auto process_tile = [&](int64_t t, const uint16_t *tile, const float *yc, const uint32_t *ys) {
+        // rows of this tile that exist; only the last tile of the streamed range can be short
+        const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
+#pragma unroll 1
+        for (int sb = 0; sb < BY / 32; ++sb) {
+            // ---- S^T tile: rows = 32 streamed y, columns = the wavefront's stationary x (XG groups of 32)
+            f32x16 s[XG];
+#pragma unroll
+            for (int g = 0; g < XG; ++g)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) s[g][q] = 0.f;
+            const uint16_t *arow = tile + sb * 32 * D;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const uint4 av = *reinterpret_cast<const uint4 *>(arow + a_off[kk & 3] + (kk >> 2) * 64);
+#pragma unroll
+                for (int g = 0; g < XG; ++g)
+                    s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(xr[g][kk]), s[g], 0, 0, 0);
+            }
+            // accumulator register q of lane (lo, hi) holds y = sb*32 + (q/4)*8 + hi*4 + q%4
+            const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
+            const bool ragged = rows_here - sb * 32 < 32;  // wave-uniform
+
+            if (MODE == MODE_FWD) {
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    if (ragged) {  // rows past the end do not take part
+                        asm volatile("" ::: "memory");  // keep this a branch: full tiles must not pay for the selects
+#pragma unroll
+                        for (int q = 0; q < 16; ++q)
+                            if ((q / 4) * 8 + (q % 4) >= rem) s[g][q] = -INFINITY;
+                    }
+                    float tm = max3(s[g][0], s[g][1], s[g][2]);
+#pragma unroll
+                    for (int q = 3; q < 15; q += 2) tm = max3(tm, s[g][q], s[g][q + 1]);
+                    const float mn = max3(run_m[g], tm * kLog2e, s[g][15] * kLog2e);
+                    if (mn > -INFINITY) {
+                        float part = 0.f;
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) part += __builtin_amdgcn_exp2f(fmaf(s[g][q], kLog2e, -mn));
+                        run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + part;
+                        run_m[g] = mn;
+                    }
+                }
+            } else {
+                // ---- probabilities (DH) or coefficients (DE), rounded to bf16, as the B operand of the second product
+                uint32_t gp[XG][8];
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    float v[16];
+                    if (MODE == MODE_DH) {
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_exp2f(fmaf(s[g][q], kLog2e, cx[g]));
+                        if (ragged) {
+                            asm volatile("" ::: "memory");  // keep this a branch: full tiles must not pay for the selects
+#pragma unroll
+                            for (int q = 0; q < 16; ++q)
+                                if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
+                        }
+                    } else {
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) {
+                            const float4 cy = *reinterpret_cast<const float4 *>(&yc[sb * 32 + qq * 8 + hi * 4]);
+                            const uint4 sg = *reinterpret_cast<const uint4 *>(&ys[sb * 32 + qq * 8 + hi * 4]);
+                            v[qq * 4 + 0] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 0], kLog2e, cy.x))) | sg.x);
+                            v[qq * 4 + 1] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 1], kLog2e, cy.y))) | sg.y);
+                            v[qq * 4 + 2] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 2], kLog2e, cy.z))) | sg.z);
+                            v[qq * 4 + 3] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 3], kLog2e, cy.w))) | sg.w);
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < 16; q += 2) gp[g][q / 2] = pack2(v[q], v[q + 1]);
+                }
+                // ---- out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const uint16_t *tp = tbase + t_off[mb & 1] + (mb >> 1) * 64;
+                        const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)tp);
+                        const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tp + 8 * D));
+                        const s16x8 r = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+                        bf16x8 av;
+                        __builtin_memcpy(&av, &r, 16);
+#pragma unroll
+                        for (int g = 0; g < XG; ++g) {
+                            const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
+                            acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
+                        }
+                    }
+                }
+            }
         }
     };
 
     if (t_begin < t_end) {
-        load_tile(t_begin);
-        store_tile(0);
+        fetch_rows(t_begin);
+        issue_tile(t_begin, tileA);
+        publish_consts(ycA, ysA);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-
-    for (int64_t t = t_begin; t < t_end; ++t) {
-        const int buf = (int)((t - t_begin) & 1);
-        if (t + 1 < t_end) load_tile(t + 1);
-
-#pragma unroll
-        for (int sb = 0; sb < BY / 32; ++sb) {
-            // ---- S^T tile: rows = 32 streamed y, columns = the wavefront's 32 stationary x
-            f32x16 s;
-#pragma unroll
-            for (int q = 0; q < 16; ++q) s[q] = 0.f;
-            const uint16_t *arow = &ytile[buf][(sb * 32 + lo) * ROW + hi * 8];
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const uint4 av = *reinterpret_cast<const uint4 *>(arow + kk * 16);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(xr[kk]), s, 0, 0, 0);
-            }
-            // accumulator register q of lane (lo, hi) holds y = sb*32 + (q/4)*8 + hi*4 + q%4
-
-            if (MODE == MODE_FWD) {
-                const int64_t ybase = t * BY + sb * 32 + hi * 4;
-                if (t * BY + sb * 32 + 32 > n_y) {  // ragged last tile: rows past the end do not take part
-#pragma unroll
-                    for (int q = 0; q < 16; ++q)
-                        if (ybase + (q / 4) * 8 + (q % 4) >= n_y) s[q] = -INFINITY;
-                }
-                float tm = s[0];
-#pragma unroll
-                for (int q = 1; q < 16; ++q) tm = fmaxf(tm, s[q]);
-                const float mn = fmaxf(run_m, tm * kLog2e);
-                if (mn > -INFINITY) {
-                    float part = 0.f;
-#pragma unroll
-                    for (int q = 0; q < 16; ++q) part += __builtin_amdgcn_exp2f(fmaf(s[q], kLog2e, -mn));
-                    run_s = run_s * __builtin_amdgcn_exp2f(run_m - mn) + part;
-                    run_m = mn;
-                }
-            } else {
-                // ---- probabilities (DH) or coefficients (DE), rounded to bf16, as the B operand of the second product
-                uint32_t gp[8];
-                if (MODE == MODE_DH) {
-#pragma unroll
-                    for (int q = 0; q < 16; q += 2)
-                        gp[q / 2] = pack2(__builtin_amdgcn_exp2f(fmaf(s[q], kLog2e, cx)),
-                                          __builtin_amdgcn_exp2f(fmaf(s[q + 1], kLog2e, cx)));
-                } else {
-#pragma unroll
-                    for (int qq = 0; qq < 4; ++qq) {
-                        const float4 cy = *reinterpret_cast<const float4 *>(&yconst[buf][sb * 32 + qq * 8 + hi * 4]);
-                        const uint4 sg = *reinterpret_cast<const uint4 *>(&ysign[buf][sb * 32 + qq * 8 + hi * 4]);
-                        const float g0 = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[qq * 4 + 0], kLog2e, cy.x))) | sg.x);
-                        const float g1 = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[qq * 4 + 1], kLog2e, cy.y))) | sg.y);
-                        const float g2 = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[qq * 4 + 2], kLog2e, cy.z))) | sg.z);
-                        const float g3 = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[qq * 4 + 3], kLog2e, cy.w))) | sg.w);
-                        gp[qq * 2 + 0] = pack2(g0, g1);
-                        gp[qq * 2 + 1] = pack2(g2, g3);
-                    }
-                }
-                // ---- out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
-                const int j = lane & 15, ta = j >> 2, tb = j & 3, cb = (lane >> 4) & 1;
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    const uint4 bv = make_uint4(gp[k2 * 4 + 0], gp[k2 * 4 + 1], gp[k2 * 4 + 2], gp[k2 * 4 + 3]);
-                    const uint16_t *tbase = &ytile[buf][(sb * 32 + k2 * 16 + hi * 4 + ta) * ROW + cb * 16 + tb * 4];
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        typedef s16x4 __attribute__((address_space(3))) * lds_v4;
-                        const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + mb * 32));
-                        const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + mb * 32 + 8 * ROW));
-                        const s16x8 r = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        bf16x8 av;
-                        __builtin_memcpy(&av, &r, 16);
-                        acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[mb], 0, 0, 0);
-                    }
-                }
-            }
+    if (DUAL) {
+        for (int64_t t = t_begin; t < t_end; t += 2) {
+            if (t + 1 < t_end) issue_tile(t + 1, tileB);
+            process_tile(t, tileA, ycA, ysA);
+            if (t + 1 < t_end) publish_consts(ycB, ysB);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (t + 1 >= t_end) break;
+            if (t + 2 < t_end) issue_tile(t + 2, tileA);
+            process_tile(t + 1, tileB, ycB, ysB);
+            if (t + 2 < t_end) publish_consts(ycA, ysA);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
         }
-
-        if (t + 1 < t_end) store_tile(buf ^ 1);
-        __syncthreads();
+    } else {
+        for (int64_t t = t_begin; t < t_end; ++t) {
+            const bool odd = ((t - t_begin) & 1) != 0;
+            if (t + 1 < t_end) issue_tile(t + 1, odd ? tileA : tileB);
+            process_tile(t, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA);
+            if (t + 1 < t_end) publish_consts(odd ? ycA : ycB, odd ? ysA : ysB);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
     }
 
     // =====================================================================================================  epilogues
     if (MODE == MODE_FWD) {
-        // merge the two halves of the candidates that lanes (lo,0) and (lo,1) hold for the same position
-        {
-            const float m2 = __shfl_xor(run_m, 32, 64), s2 = __shfl_xor(run_s, 32, 64);
-            const float M = fmaxf(run_m, m2);
-            if (M > -INFINITY) {
-                run_s = run_s * __builtin_amdgcn_exp2f(run_m - M) + s2 * __builtin_amdgcn_exp2f(m2 - M);
-                run_m = M;
+#pragma unroll
+        for (int g = 0; g < XG; ++g) {
+            // merge the two halves of the candidates that lanes (lo,0) and (lo,1) hold for the same position
+            float rm = run_m[g], rs = run_s[g];
+            {
+                const float m2 = __shfl_xor(rm, 32, 64), s2 = __shfl_xor(rs, 32, 64);
+                const float M = fmaxf(rm, m2);
+                if (M > -INFINITY) {
+                    rs = rs * __builtin_amdgcn_exp2f(rm - M) + s2 * __builtin_amdgcn_exp2f(m2 - M);
+                    rm = M;
+                }
             }
-        }
-        if (a.splits > 1) {
-            if (x_ok && hi == 0) {
-                a.part_m[(int64_t)split * a.N + x] = run_m;
-                a.part_s[(int64_t)split * a.N + x] = run_s;
+            const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+            if (a.splits > 1) {
+                if (x_ok[g] && hi == 0) {
+                    a.part_m[(int64_t)split * a.N + x] = rm;
+                    a.part_s[(int64_t)split * a.N + x] = rs;
+                }
+                continue;
             }
-            return;
-        }
-        float op = 0.f;
-        if (x_ok) op = half_row_dot<D>(xr, a.E + (int64_t)a.tgt[xrow] * D, hi);
-        op += __shfl_xor(op, 32, 64);
-        if (x_ok && hi == 0) {
-            const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[xrow] : 1.f);
-            const float o2 = op * kLog2e;
-            const float M = (w != 0.f) ? fmaxf(run_m, o2) : run_m;
-            const float tot = run_s * __builtin_amdgcn_exp2f(run_m - M) + w * __builtin_amdgcn_exp2f(o2 - M);
-            const float l = (M + __builtin_amdgcn_logf(tot)) * kLn2;
-            a.lse[xrow] = l;
-            a.loss[xrow] = l - op;
+            float op = 0.f;
+            if (x_ok[g]) op = half_row_dot<D>(xr[g], a.E + (int64_t)a.tgt[xrow[g]] * D, hi);
+            op += __shfl_xor(op, 32, 64);
+            if (x_ok[g] && hi == 0) {
+                const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[xrow[g]] : 1.f);
+                const float o2 = op * kLog2e;
+                const float M = (w != 0.f) ? fmaxf(rm, o2) : rm;
+                const float tot = rs * __builtin_amdgcn_exp2f(rm - M) + w * __builtin_amdgcn_exp2f(o2 - M);
+                const float l = (M + __builtin_amdgcn_logf(tot)) * kLn2;
+                a.lse[xrow[g]] = l;
+                a.loss[xrow[g]] = l - op;
+            }
         }
     } else if (MODE == MODE_DH) {
-        if (a.splits > 1) {
-            if (x_ok) {
-                float *dst = a.part_dH + ((int64_t)split * a.N + x) * D;
+#pragma unroll
+        for (int g = 0; g < XG; ++g) {
+            const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+            if (a.splits > 1) {
+                if (x_ok[g]) {
+                    float *dst = a.part_dH + ((int64_t)split * a.N + x) * D;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq)
+                            *reinterpret_cast<float4 *>(dst + mb * 32 + qq * 8 + hi * 4) = make_float4(
+                                acc[g][mb][qq * 4], acc[g][mb][qq * 4 + 1], acc[g][mb][qq * 4 + 2], acc[g][mb][qq * 4 + 3]);
+                }
+                continue;
+            }
+            float op = 0.f;
+            const uint16_t *erow = a.E + (x_ok[g] ? (int64_t)a.tgt[xrow[g]] : 0) * D;
+            if (x_ok[g]) op = half_row_dot<D>(xr[g], erow, hi);
+            op += __shfl_xor(op, 32, 64);
+            if (x_ok[g]) {
+                const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[xrow[g]] : 1.f);
+                const float pp = __builtin_amdgcn_exp2f(fmaf(op, kLog2e, cx[g]));
+                const float cpos = w * pp - 1.f;  // coefficient of the correct item before the upstream gradient
+                const float gg = a.g ? a.g[xrow[g]] : 1.f;
+                if (hi == 0) a.coef[xrow[g]] = gg * cpos;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                    for (int qq = 0; qq < 4; ++qq)
-                        *reinterpret_cast<float4 *>(dst + mb * 32 + qq * 8 + hi * 4) =
-                            make_float4(acc[mb][qq * 4], acc[mb][qq * 4 + 1], acc[mb][qq * 4 + 2], acc[mb][qq * 4 + 3]);
-            }
-            return;
-        }
-        float op = 0.f;
-        const uint16_t *erow = a.E + (x_ok ? (int64_t)a.tgt[xrow] : 0) * D;
-        if (x_ok) op = half_row_dot<D>(xr, erow, hi);
-        op += __shfl_xor(op, 32, 64);
-        if (x_ok) {
-            const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[xrow] : 1.f);
-            const float pp = __builtin_amdgcn_exp2f(fmaf(op, kLog2e, cx));
-            const float cpos = w * pp - 1.f;  // coefficient of the correct item before the upstream gradient
-            const float g = a.g ? a.g[xrow] : 1.f;
-            if (hi == 0) a.coef[xrow] = g * cpos;
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int qq = 0; qq < 4; ++qq) {
-                    const int col = mb * 32 + qq * 8 + hi * 4;
-                    const uint2 ev = *reinterpret_cast<const uint2 *>(erow + col);
-                    const float v0 = g * fmaf(cpos, bf16_lo(ev.x), acc[mb][qq * 4 + 0]);
-                    const float v1 = g * fmaf(cpos, bf16_hi(ev.x), acc[mb][qq * 4 + 1]);
-                    const float v2 = g * fmaf(cpos, bf16_lo(ev.y), acc[mb][qq * 4 + 2]);
-                    const float v3 = g * fmaf(cpos, bf16_hi(ev.y), acc[mb][qq * 4 + 3]);
-                    if (a.dH_bf16) {
-                        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.dH) + xrow * D + col) =
-                            make_uint2(pack2(v0, v1), pack2(v2, v3));
-                    } else {
-                        *reinterpret_cast<float4 *>(static_cast<float *>(a.dH) + xrow * D + col) = make_float4(v0, v1, v2, v3);
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const int col = mb * 32 + qq * 8 + hi * 4;
+                        const uint2 ev = *reinterpret_cast<const uint2 *>(erow + col);
+                        const float v0 = gg * fmaf(cpos, bf16_lo(ev.x), acc[g][mb][qq * 4 + 0]);
+                        const float v1 = gg * fmaf(cpos, bf16_hi(ev.x), acc[g][mb][qq * 4 + 1]);
+                        const float v2 = gg * fmaf(cpos, bf16_lo(ev.y), acc[g][mb][qq * 4 + 2]);
+                        const float v3 = gg * fmaf(cpos, bf16_hi(ev.y), acc[g][mb][qq * 4 + 3]);
+                        if (a.dH_bf16) {
+                            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(a.dH) + xrow[g] * D + col) =
+                                make_uint2(pack2(v0, v1), pack2(v2, v3));
+                        } else {
+                            *reinterpret_cast<float4 *>(static_cast<float *>(a.dH) + xrow[g] * D + col) =
+                                make_float4(v0, v1, v2, v3);
+                        }
                     }
-                }
+            }
         }
     } else {
         // dE_neg^T sits in the accumulators with the hidden index in registers and the candidate row on the lanes.
         // Turn each 32x32 block round through LDS (the streamed tiles are dead by now) so that one atomic
         // instruction adds 32 consecutive floats to each of two table rows.
-        float *tbuf = reinterpret_cast<float *>(&ytile[0][0]) + wave * (32 * 33);
-        static_assert(sizeof(ytile) >= 4 * 32 * 33 * sizeof(float), "staging tiles too small for the dE transpose");
-        __shared__ int64_t xrow_s[kXPerBlock];
-        xrow_s[wave * kXPerWave + lo] = x_ok ? xrow : -1;  // both half-waves write the same value
+        float *tbuf = reinterpret_cast<float *>((wave & 1) ? tileB : tileA) + (wave >> 1) * (32 * 33);  // 2 per buffer
+#pragma unroll
+        for (int g = 0; g < XG; ++g) xrow_s[(wave * XG + g) * 32 + lo] = x_ok[g] ? xrow[g] : -1;  // both half-waves agree
         __syncthreads();
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
+        for (int g = 0; g < XG; ++g) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) tbuf[lo * 33 + (q / 4) * 8 + hi * 4 + (q % 4)] = acc[mb][q];
-            __syncthreads();
+            for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int xr_local = r * 2 + hi;
-                const int64_t row = xrow_s[wave * kXPerWave + xr_local];
-                const float v = tbuf[xr_local * 33 + lo];
-                if (row >= 0) unsafeAtomicAdd(a.dE + row * D + mb * 32 + lo, v);
+                for (int q = 0; q < 16; ++q) tbuf[lo * 33 + (q / 4) * 8 + hi * 4 + (q % 4)] = acc[g][mb][q];
+                __syncthreads();
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int xl = r * 2 + hi;
+                    const int64_t row = xrow_s[(wave * XG + g) * 32 + xl];
+                    const float v = tbuf[xl * 33 + lo];
+                    if (row >= 0) unsafeAtomicAdd(a.dE + row * D + mb * 32 + lo, v);
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
 }
@@ -614,175 +814,87 @@ __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------------------------------
-// dE of the correct items: dE[tgt_i] += coef_i * H_i.  Targets follow a power law, so plain atomics would serialise
-// on a few hot rows.  Each block counts its 256 targets in an LDS hash table; a target met once is added straight
-// away (one wavefront per row, consecutive addresses), a target met several times has its positions gathered into a
-// segment that one wavefront sums in registers before a single atomic row add.
-constexpr int kPosChunk = 256;
-constexpr int kPosSlots = 512;
-
-template <int D>
-__global__ __launch_bounds__(256) void pos_scatter_kernel(TileArgs a)
+// Blocks of one kernel instantiation that the whole chip holds at once (queried once).
+template <typename K>
+int resident_blocks(K kernel, int threads)
 {
-    constexpr int CPL = D / 64;  // columns per lane: lane owns columns lane*CPL .. +CPL of a row
-    __shared__ int32_t hkey[kPosSlots];
-    __shared__ int32_t hcnt[kPosSlots];
-    __shared__ int32_t hoff[kPosSlots];
-    __shared__ int32_t hcur[kPosSlots];
-    __shared__ int32_t grouped[kPosChunk];   // position rows of the repeated targets, segment after segment
-    __shared__ int32_t seg_key[kPosChunk / 2], seg_off[kPosChunk / 2], seg_len[kPosChunk / 2];
-    __shared__ int32_t n_grouped, n_segs;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
-    const int64_t e = (int64_t)blockIdx.x * kPosChunk + tid;
-    if ((int64_t)blockIdx.x * kPosChunk >= n_pos) return;
-    const bool have = e < n_pos;
-    const int32_t row = have ? (int32_t)pos_row(a, e) : -1;
-    const int32_t key = have ? a.tgt[row] : -1;
-
-    for (int s = tid; s < kPosSlots; s += 256) {
-        hkey[s] = -1;
-        hcnt[s] = 0;
-        hcur[s] = 0;
-    }
-    if (tid == 0) {
-        n_grouped = 0;
-        n_segs = 0;
-    }
-    __syncthreads();
-    int slot = -1;
-    bool leader = false;
-    if (have) {
-        uint32_t h = hash_id(key, kPosSlots);
-        for (int probe = 0; probe < kPosSlots; ++probe) {
-            const int32_t prev = atomicCAS(&hkey[h], -1, key);
-            if (prev == -1 || prev == key) {
-                slot = (int)h;
-                leader = (prev == -1);
-                atomicAdd(&hcnt[h], 1);
-                break;
-            }
-            h = (h + 1) & (kPosSlots - 1);
-        }
-    }
-    __syncthreads();
-    const int n_same = have ? hcnt[slot] : 0;
-    if (leader && n_same > 1) {
-        const int off = atomicAdd(&n_grouped, n_same);
-        const int sg = atomicAdd(&n_segs, 1);
-        hoff[slot] = off;
-        seg_key[sg] = key;
-        seg_off[sg] = off;
-        seg_len[sg] = n_same;
-    }
-    __syncthreads();
-    if (n_same > 1) grouped[hoff[slot] + atomicAdd(&hcur[slot], 1)] = row;
-    __syncthreads();
-
-    // ---- targets met once: the wavefront walks over its lanes' entries, four rows in flight
-    {
-        uint64_t todo = __ballot(n_same == 1);
-        while (todo) {
-            int32_t r4[4], k4[4];
-            float c4[4];
-            float h4[4][CPL];
-            int n = 0;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                r4[u] = -1;
-                if (todo) {
-                    const int src = __ffsll((unsigned long long)todo) - 1;
-                    todo &= todo - 1;
-                    r4[u] = __shfl(row, src, 64);
-                    k4[u] = __shfl(key, src, 64);
-                    n = u + 1;
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (u < n) {
-                    c4[u] = a.coef[r4[u]];
-#pragma unroll
-                    for (int t = 0; t < CPL; ++t) h4[u][t] = load1(a.H + (int64_t)r4[u] * D + lane * CPL + t);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (u < n) {
-#pragma unroll
-                    for (int t = 0; t < CPL; ++t)
-                        unsafeAtomicAdd(a.dE + (int64_t)k4[u] * D + lane * CPL + t, c4[u] * h4[u][t]);
-                }
-            }
-        }
-    }
-    // ---- repeated targets: one wavefront per segment
-    const int segs = n_segs;
-    for (int sg = wave; sg < segs; sg += 4) {
-        const int off = seg_off[sg], len = seg_len[sg];
-        float accv[CPL];
-#pragma unroll
-        for (int t = 0; t < CPL; ++t) accv[t] = 0.f;
-        for (int j0 = 0; j0 < len; j0 += 4) {
-            float c4[4];
-            float h4[4][CPL];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                c4[u] = 0.f;
-#pragma unroll
-                for (int t = 0; t < CPL; ++t) h4[u][t] = 0.f;
-                if (j0 + u < len) {
-                    const int32_t r = grouped[off + j0 + u];
-                    c4[u] = a.coef[r];
-#pragma unroll
-                    for (int t = 0; t < CPL; ++t) h4[u][t] = load1(a.H + (int64_t)r * D + lane * CPL + t);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int t = 0; t < CPL; ++t) accv[t] = fmaf(c4[u], h4[u][t], accv[t]);
-        }
-        const int64_t k = seg_key[sg];
-#pragma unroll
-        for (int t = 0; t < CPL; ++t) unsafeAtomicAdd(a.dE + k * D + lane * CPL + t, accv[t]);
-    }
+    int per_cu = 0, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1)
+        return 256;
+    return per_cu * prop.multiProcessorCount;
 }
 
-// ---------------------------------------------------------------------------------------------------------------------
-template <int D>
-hipError_t launch_for_d(int pass, const TileArgs &a, hipStream_t stream)
+// Split factor in [1, max_splits] that wastes the least of the last round of blocks; ties go to the smaller factor,
+// and a factor is only raised for a gain of at least five percent.
+inline int pick_splits(int64_t xblocks, int max_splits, int slots)
 {
-    constexpr int BY = (D <= 128) ? 64 : 32;
-    const int64_t n_x = (pass == TILE_PASS_DE) ? a.n_cols : a.N;
-    const int64_t xblocks = (n_x + kXPerBlock - 1) / kXPerBlock;
+    if (xblocks * 4 > slots) return 1;  // enough blocks already: a split costs partial results and a merge
+    int best = 1;
+    double best_eff = 0.0;
+    for (int s = 1; s <= max_splits; ++s) {
+        const int64_t blocks = xblocks * s;
+        const int64_t rounds = (blocks + slots - 1) / slots;
+        const double eff = (double)blocks / (double)(rounds * slots);
+        if (eff > best_eff * 1.05) {
+            best_eff = eff;
+            best = s;
+        }
+    }
+    return best;
+}
+
+template <int D, int MODE, int BY, int NW, int XG, int MINB, bool DUAL>
+hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
+{
+    constexpr int XPB = NW * XG * 32;
+    const int64_t xblocks = (n_x + XPB - 1) / XPB;
     if (xblocks == 0) return hipSuccess;
-    const dim3 grid((unsigned)(xblocks * a.splits)), block(kThreads);
+    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>, NW * 64);
+    // the dE pass pays for every split with a full set of atomics on its rows: stay within about one block per CU
+    a.splits = (MODE == MODE_DE) ? pick_splits(xblocks, a.splits, slots < 320 ? slots : 320) : pick_splits(xblocks, a.splits, slots);
+    int64_t blocks = xblocks * a.splits;
+    if (MODE == MODE_DE) {
+        a.de_blocks = blocks;
+        blocks += (a.N + kPosChunk - 1) / kPosChunk;
+    }
+    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
+{
+    constexpr int BY = 8192 / D;               // 16 KiB of bf16 per tile buffer: 128 rows at d = 64, 32 rows at d = 256
+    constexpr int MINB = (D <= 64) ? 3 : 2;    // register budget per wavefront: 168 at d = 64, else 256
+    constexpr bool DUAL = (D <= 128);
+    constexpr int XG_FWD = (D >= 256) ? 2 : 1; // d = 256 is bound by LDS reads: share them between two groups
+    hipError_t e = hipSuccess;
     switch (pass) {
     case TILE_PASS_FWD:
-        hipLaunchKernelGGL((tile_kernel<D, MODE_FWD, BY>), grid, block, 0, stream, a);
-        if (a.splits > 1)
+        if (XG_FWD == 2 && ((a.N + 255) / 256) * a.splits >= 240)
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_FWD, MINB, DUAL>(a, a.N, stream);
+        else
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
+        if (e == hipSuccess && a.splits > 1) {
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
-        break;
+            e = hipGetLastError();
+        }
+        return e;
     case TILE_PASS_DH:
-        hipLaunchKernelGGL((tile_kernel<D, MODE_DH, BY>), grid, block, 0, stream, a);
-        if (a.splits > 1) {
+        e = launch_tile_kernel<D, MODE_DH, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
+        if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             hipLaunchKernelGGL((dh_merge_kernel<D>), dim3((unsigned)((a.N + PPB - 1) / PPB)), dim3(256), 0, stream, a);
+            e = hipGetLastError();
         }
-        break;
+        return e;
     case TILE_PASS_DE:
-        hipLaunchKernelGGL((tile_kernel<D, MODE_DE, BY>), grid, block, 0, stream, a);
-        break;
-    case TILE_PASS_POS:
-        hipLaunchKernelGGL((pos_scatter_kernel<D>), dim3((unsigned)((a.N + kPosChunk - 1) / kPosChunk)), dim3(256), 0,
-                           stream, a);
-        break;
+        return launch_tile_kernel<D, MODE_DE, BY, 4, 1, MINB, DUAL>(a, a.n_cols, stream);
     default:
         return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 }  // namespace
