@@ -19,6 +19,8 @@
 // target: the dense tile counts those c_i copies, the definition wants the target exactly once, so
 //   sum_live exp(o) = sum_k exp(o_ik) + w_i exp(o+_i),   coefficient of the correct item = g_i (w_i p+_i - 1).
 // With collision masking off w_i = 1; in full-catalogue mode the target is already one of the columns and w_i = 0.
+#include <stdlib.h>
+
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
 
@@ -34,6 +36,10 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 
 enum { MODE_FWD = 0, MODE_DH = 1, MODE_DE = 2 };
+
+// Compile-time tags: a full streamed tile, or the short last tile whose missing rows are masked.
+struct Full { static constexpr bool value = false; };
+struct Ragged { static constexpr bool value = true; };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {
@@ -190,6 +196,7 @@ __device__ __forceinline__ float max3(float x, float y, float z)
 template <int D, int MODE, int BY, int NW, int XG, int MINB, bool DUAL>
 __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 {
+    constexpr bool SWP = (D <= 128);       // registers allow a second score tile in flight up to d = 128
     constexpr int KK = D / 16;             // k-steps of the score product
     constexpr int MB = D / 32;             // 32-row output blocks of the second product
     constexpr int CPR = D / 8;             // 16-byte chunks per row
@@ -333,101 +340,131 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     for (int m2 = 0; m2 < 2; ++m2)
         t_off[m2] = (hi * 4 + ta) * D + (((m2 * 4 + cb * 2 + (tb >> 1)) ^ swz(hi * 4 + ta)) * 8) + (tb & 1) * 4;
 
-    auto process_tile = [&](int64_t t, const uint16_t *tile, const float *yc, const uint32_t *ys) {
-        // rows of this tile that exist; only the last tile of the streamed range can be short
-        const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
-#pragma unroll 1
-        for (int sb = 0; sb < BY / 32; ++sb) {
-            // ---- S^T tile: rows = 32 streamed y, columns = the wavefront's stationary x (XG groups of 32)
-            f32x16 s[XG];
+    // A tile is NSB sub-tiles of 32 streamed rows.  The sub-tile loop is unrolled and software-pipelined inside the
+    // wavefront: the matrix instructions of the next score tile are issued before the exponentials of the current one,
+    // so the matrix pipe (asynchronous) works on them, and on the second product of the previous sub-tile, while the
+    // vector unit does the softmax arithmetic.  Matrix and vector work per sub-tile are about equal at d = 64
+    // (measured 122 ns against 120 ns per SIMD), and two or three wavefronts per SIMD do not overlap them on their own.
+    // The short last tile of the streamed range takes a separate copy of the code (RAGGED), so that full tiles have
+    // no branch or select in this loop.
+    constexpr int NSB = BY / 32;
+    auto scores = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG]) {
+#pragma unroll
+        for (int g = 0; g < XG; ++g)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) sv[g][q] = 0.f;
+        const uint16_t *arow = tile + sb * 32 * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const uint4 av = *reinterpret_cast<const uint4 *>(arow + a_off[kk & 3] + (kk >> 2) * 64);
 #pragma unroll
             for (int g = 0; g < XG; ++g)
+                sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
+        }
+    };
+    // softmax arithmetic of one sub-tile, and (backward) its second product
+    auto consume = [&](const uint16_t *tile, const float *yc, const uint32_t *ys, int sb, f32x16 (&sv)[XG], int rows_here,
+                       auto ragged_tag) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+        // accumulator register q of lane (lo, hi) holds y = sb*32 + (q/4)*8 + hi*4 + q%4
+        const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
+        if (MODE == MODE_FWD) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) s[g][q] = 0.f;
-            const uint16_t *arow = tile + sb * 32 * D;
+            for (int g = 0; g < XG; ++g) {
+                if (RAGGED) {  // rows past the end do not take part
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const uint4 av = *reinterpret_cast<const uint4 *>(arow + a_off[kk & 3] + (kk >> 2) * 64);
+                    for (int q = 0; q < 16; ++q)
+                        if ((q / 4) * 8 + (q % 4) >= rem) sv[g][q] = -INFINITY;
+                }
+                float tm = max3(sv[g][0], sv[g][1], sv[g][2]);
 #pragma unroll
-                for (int g = 0; g < XG; ++g)
-                    s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(xr[g][kk]), s[g], 0, 0, 0);
+                for (int q = 3; q < 15; q += 2) tm = max3(tm, sv[g][q], sv[g][q + 1]);
+                const float mn = max3(run_m[g], tm * kLog2e, sv[g][15] * kLog2e);
+                if (!RAGGED || mn > -INFINITY) {  // a full sub-tile always has a finite maximum
+                    float part = 0.f;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) part += __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, -mn));
+                    run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + part;
+                    run_m[g] = mn;
+                }
             }
-            // accumulator register q of lane (lo, hi) holds y = sb*32 + (q/4)*8 + hi*4 + q%4
-            const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
-            const bool ragged = rows_here - sb * 32 < 32;  // wave-uniform
-
-            if (MODE == MODE_FWD) {
+        } else {
+            // ---- probabilities (DH) or coefficients (DE), rounded to bf16, as the B operand of the second product
+            uint32_t gp[XG][8];
 #pragma unroll
-                for (int g = 0; g < XG; ++g) {
-                    if (ragged) {  // rows past the end do not take part
-                        asm volatile("" ::: "memory");  // keep this a branch: full tiles must not pay for the selects
+            for (int g = 0; g < XG; ++g) {
+                float v[16];
+                if (MODE == MODE_DH) {
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, cx[g]));
+                    if (RAGGED) {
 #pragma unroll
                         for (int q = 0; q < 16; ++q)
-                            if ((q / 4) * 8 + (q % 4) >= rem) s[g][q] = -INFINITY;
+                            if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
                     }
-                    float tm = max3(s[g][0], s[g][1], s[g][2]);
+                } else {
 #pragma unroll
-                    for (int q = 3; q < 15; q += 2) tm = max3(tm, s[g][q], s[g][q + 1]);
-                    const float mn = max3(run_m[g], tm * kLog2e, s[g][15] * kLog2e);
-                    if (mn > -INFINITY) {
-                        float part = 0.f;
-#pragma unroll
-                        for (int q = 0; q < 16; ++q) part += __builtin_amdgcn_exp2f(fmaf(s[g][q], kLog2e, -mn));
-                        run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + part;
-                        run_m[g] = mn;
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const float4 cy = *reinterpret_cast<const float4 *>(&yc[sb * 32 + qq * 8 + hi * 4]);
+                        const uint4 sg = *reinterpret_cast<const uint4 *>(&ys[sb * 32 + qq * 8 + hi * 4]);
+                        v[qq * 4 + 0] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 0], kLog2e, cy.x))) | sg.x);
+                        v[qq * 4 + 1] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 1], kLog2e, cy.y))) | sg.y);
+                        v[qq * 4 + 2] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 2], kLog2e, cy.z))) | sg.z);
+                        v[qq * 4 + 3] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 3], kLog2e, cy.w))) | sg.w);
                     }
                 }
-            } else {
-                // ---- probabilities (DH) or coefficients (DE), rounded to bf16, as the B operand of the second product
-                uint32_t gp[XG][8];
 #pragma unroll
-                for (int g = 0; g < XG; ++g) {
-                    float v[16];
-                    if (MODE == MODE_DH) {
+                for (int q = 0; q < 16; q += 2) gp[g][q / 2] = pack2(v[q], v[q + 1]);
+            }
+            // ---- out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
 #pragma unroll
-                        for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_exp2f(fmaf(s[g][q], kLog2e, cx[g]));
-                        if (ragged) {
-                            asm volatile("" ::: "memory");  // keep this a branch: full tiles must not pay for the selects
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
 #pragma unroll
-                            for (int q = 0; q < 16; ++q)
-                                if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
-                        }
-                    } else {
+                for (int mb = 0; mb < MB; ++mb) {
+                    const uint16_t *tp = tbase + t_off[mb & 1] + (mb >> 1) * 64;
+                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)tp);
+                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tp + 8 * D));
+                    const s16x8 r = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    bf16x8 av;
+                    __builtin_memcpy(&av, &r, 16);
 #pragma unroll
-                        for (int qq = 0; qq < 4; ++qq) {
-                            const float4 cy = *reinterpret_cast<const float4 *>(&yc[sb * 32 + qq * 8 + hi * 4]);
-                            const uint4 sg = *reinterpret_cast<const uint4 *>(&ys[sb * 32 + qq * 8 + hi * 4]);
-                            v[qq * 4 + 0] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 0], kLog2e, cy.x))) | sg.x);
-                            v[qq * 4 + 1] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 1], kLog2e, cy.y))) | sg.y);
-                            v[qq * 4 + 2] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 2], kLog2e, cy.z))) | sg.z);
-                            v[qq * 4 + 3] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(s[g][qq * 4 + 3], kLog2e, cy.w))) | sg.w);
-                        }
-                    }
-#pragma unroll
-                    for (int q = 0; q < 16; q += 2) gp[g][q / 2] = pack2(v[q], v[q + 1]);
-                }
-                // ---- out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
-#pragma unroll
-                for (int k2 = 0; k2 < 2; ++k2) {
-                    const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) {
-                        const uint16_t *tp = tbase + t_off[mb & 1] + (mb >> 1) * 64;
-                        const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)tp);
-                        const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tp + 8 * D));
-                        const s16x8 r = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
-                        bf16x8 av;
-                        __builtin_memcpy(&av, &r, 16);
-#pragma unroll
-                        for (int g = 0; g < XG; ++g) {
-                            const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
-                            acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
-                        }
+                    for (int g = 0; g < XG; ++g) {
+                        const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
+                        acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
                     }
                 }
             }
         }
     };
+    auto process_tile = [&](int64_t t, const uint16_t *tile, const float *yc, const uint32_t *ys, auto ragged_tag) {
+        // rows of this tile that exist; only the last tile of the streamed range can be short
+        const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
+        if (SWP) {
+            f32x16 sa[XG], sb_[XG];
+            scores(tile, 0, sa);
+#pragma unroll
+            for (int sb = 0; sb < NSB; sb += 2) {
+                if (sb + 1 < NSB) scores(tile, sb + 1, sb_);
+                consume(tile, yc, ys, sb, sa, rows_here, ragged_tag);
+                if (sb + 1 < NSB) {
+                    if (sb + 2 < NSB) scores(tile, sb + 2, sa);
+                    consume(tile, yc, ys, sb + 1, sb_, rows_here, ragged_tag);
+                }
+            }
+        } else {
+#pragma unroll 1
+            for (int sb = 0; sb < NSB; ++sb) {
+                f32x16 sv[XG];
+                scores(tile, sb, sv);
+                consume(tile, yc, ys, sb, sv, rows_here, ragged_tag);
+            }
+        }
+    };
+
+    // The last tile of the whole streamed range may be short; it is left out of the main loop and handled after it.
+    const bool tail_ragged = (n_y % BY) != 0 && t_end == n_tiles && t_end > t_begin;
+    const int64_t t_stop = tail_ragged ? t_end - 1 : t_end;  // tiles [t_begin, t_stop) are full
 
     if (t_begin < t_end) {
         fetch_rows(t_begin);
@@ -437,28 +474,33 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (DUAL) {
-        for (int64_t t = t_begin; t < t_end; t += 2) {
+        for (int64_t t = t_begin; t < t_stop; t += 2) {
             if (t + 1 < t_end) issue_tile(t + 1, tileB);
-            process_tile(t, tileA, ycA, ysA);
+            process_tile(t, tileA, ycA, ysA, Full{});
             if (t + 1 < t_end) publish_consts(ycB, ysB);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (t + 1 >= t_end) break;
+            if (t + 1 >= t_stop) break;
             if (t + 2 < t_end) issue_tile(t + 2, tileA);
-            process_tile(t + 1, tileB, ycB, ysB);
+            process_tile(t + 1, tileB, ycB, ysB, Full{});
             if (t + 2 < t_end) publish_consts(ycA, ysA);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
     } else {
-        for (int64_t t = t_begin; t < t_end; ++t) {
+        for (int64_t t = t_begin; t < t_stop; ++t) {
             const bool odd = ((t - t_begin) & 1) != 0;
             if (t + 1 < t_end) issue_tile(t + 1, odd ? tileA : tileB);
-            process_tile(t, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA);
+            process_tile(t, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA, Full{});
             if (t + 1 < t_end) publish_consts(odd ? ycA : ycB, odd ? ysA : ysB);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
         }
+    }
+    if (tail_ragged) {  // its rows were fetched by the step before (or by the prologue) and the barrier has passed
+        const bool odd = ((t_stop - t_begin) & 1) != 0;
+        process_tile(t_stop, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA, Ragged{});
+        __syncthreads();  // the dE epilogue reuses the tile buffers
     }
 
     // =====================================================================================================  epilogues
@@ -867,23 +909,37 @@ template <int D>
 hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
 {
     constexpr int BY = 8192 / D;               // 16 KiB of bf16 per tile buffer: 128 rows at d = 64, 32 rows at d = 256
-    constexpr int MINB = (D <= 64) ? 3 : 2;    // register budget per wavefront: 168 at d = 64, else 256
+    constexpr int MINB_F = (D <= 64) ? 3 : 2;  // forward: register budget 168 at d = 64, else 256
+    constexpr int MINB = 2;                    // backward: 256 registers per wavefront
     constexpr bool DUAL = (D <= 128);
-    constexpr int XG_FWD = (D >= 256) ? 2 : 1; // d = 256 is bound by LDS reads: share them between two groups
+    // LDS delivers about 64 bytes per clock per compute unit, half of what four SIMDs need to keep the matrix cores
+    // busy when every matrix instruction fetches a fresh operand.  Two groups of stationary rows per wavefront use
+    // each LDS operand twice; the backward accumulators leave room for that up to d = 64.
+    constexpr int XG_F = 2;
+    constexpr int XG_B = (D <= 64) ? 2 : 1;
     hipError_t e = hipSuccess;
+    // Two groups want 256 stationary rows per block: worth it when that still gives about two blocks per compute
+    // unit, either directly or because the streamed range is being split anyway.
+    auto wide = [&](int64_t n_x, bool may_split) {
+        const int64_t xb = (n_x + 255) / 256;
+        return xb >= 300 || (may_split && xb < 120 && xb * a.splits >= 480);
+    };
     switch (pass) {
     case TILE_PASS_FWD:
-        if (XG_FWD == 2 && ((a.N + 255) / 256) * a.splits >= 240)
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_FWD, MINB, DUAL>(a, a.N, stream);
+        if (wide(a.N, true))
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_F, MINB_F, DUAL>(a, a.N, stream);
         else
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB_F, DUAL>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
             e = hipGetLastError();
         }
         return e;
     case TILE_PASS_DH:
-        e = launch_tile_kernel<D, MODE_DH, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
+        if (XG_B == 2 && wide(a.N, true))
+            e = launch_tile_kernel<D, MODE_DH, BY, 4, XG_B, MINB, DUAL>(a, a.N, stream);
+        else
+            e = launch_tile_kernel<D, MODE_DH, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             hipLaunchKernelGGL((dh_merge_kernel<D>), dim3((unsigned)((a.N + PPB - 1) / PPB)), dim3(256), 0, stream, a);
@@ -891,6 +947,8 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         }
         return e;
     case TILE_PASS_DE:
+        if (XG_B == 2 && wide(a.n_cols, false))
+            return launch_tile_kernel<D, MODE_DE, BY, 4, XG_B, MINB, DUAL>(a, a.n_cols, stream);
         return launch_tile_kernel<D, MODE_DE, BY, 4, 1, MINB, DUAL>(a, a.n_cols, stream);
     default:
         return hipErrorInvalidValue;
