@@ -25,7 +25,7 @@ PEAK_F32_VALU_TFLOPS = 157.3
 
 
 def algorithmic_work(w):
-    """Flops and minimum HBM bytes of one forward+backward, counted on valid positions only.
+    """Algorithmic flops and minimum HBM bytes of one forward+backward, counted on valid positions only.
 
     flops: four GEMM-equivalents (scores forward, scores recomputed, dH, dE), 2 flop per multiply-add:
            8 * n_cand * d per valid position, n_cand = K+1 (or V for the full catalogue).
@@ -50,6 +50,47 @@ def algorithmic_work(w):
     return flops, gathered + dE_bytes + ids + per_pos
 
 
+def kernel_work(w, family):
+    """Algorithmic work of ONE launch of a kernel family: ("mfma", flops) or ("hbm", bytes).
+
+    Matrix-core kernels: 2 * n_cols * d flop per valid position and GEMM-equivalent, n_cols = K (V for the full
+    catalogue).  The forward pass is one GEMM-equivalent (scores), the dH pass two (scores recomputed, dH), the dE pass
+    one (dE; its own recomputation of the scores is overhead and does not count).
+    Row-gather kernels: the candidate rows of every valid position (K+1 rows of d elements), the ids, H, and for the
+    backward pass dH and every dE row written once.
+    """
+    nv = w.n_valid
+    esz = 4 if w.in_dtype == "f32" else 2
+    n_cols = w.V if w.neg_mode == 2 else w.K
+    gemm = 2.0 * n_cols * w.d * nv
+    if family == "tile_fwd":
+        return "mfma", gemm
+    if family == "tile_dh":
+        return "mfma", 2 * gemm
+    if family == "tile_de":
+        return "mfma", gemm
+    n_cand = w.V if w.neg_mode == 2 else w.K + 1
+    rows = float(nv) * n_cand * w.d * esz
+    ids = float(nv) * (w.K if w.neg_mode == 1 else 0) * 4
+    if family == "gather_fwd":
+        return "hbm", rows + ids + nv * w.d * esz + w.N * 13
+    if family == "gather_bwd":
+        return "hbm", rows + ids + nv * w.d * esz + float(nv) * n_cand * w.d * 4 + nv * w.d * 4 + w.N * 13
+    return "hbm", 0.0
+
+
+def measured_traffic(workload, family):
+    """HBM bytes per launch measured with rocprofv3 counters and kept under profiles/ (None when no record exists)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 4 and not line.startswith("#") and f[0] == workload and f[1] == family:
+            return float(f[2]) + float(f[3])
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +100,8 @@ def main() -> int:
     ap.add_argument("--algo", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run five plain device copies of BYTES (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -71,6 +114,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists for the product path)", file=sys.stderr)
         return 2
+
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 5}))
+        return 0
 
     import paper_2509_09682_amd as P
     from hip_harness import to_device
@@ -120,25 +172,30 @@ def main() -> int:
     torch.cuda.synchronize()
     memset_ms = z0.elapsed_time(z1)
 
+    # per-kernel durations: the same K steps once more with the library's event brackets switched on
+    P.cce_neg_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    fam = P.cce_neg_profile_read()
+    P.cce_neg_profile_enable(False)
+    kernels = {k: {"avg_ms": ms / n, "launches_per_step": n / args.steps} for k, (ms, n) in fam.items()}
+    dominant = max(fam, key=lambda k: fam[k][0])
+    dom_ms = fam[dominant][0] / fam[dominant][1]
+
     flops, bytes_min = algorithmic_work(w)
-    gather_bound = (w.neg_mode == 1)
-    # dominant launch = the backward call (3 of the 4 GEMM-equivalents; all of the dE traffic)
-    if gather_bound:
-        _, b_all = algorithmic_work(w)
-        # backward's share of the bytes: one gather pass + dE + dH + half of the per-position vectors
-        esz = 4 if w.in_dtype == "f32" else 2
-        n_cand = w.K + 1
-        b_bwd = w.n_valid * n_cand * w.d * esz + w.n_valid * n_cand * w.d * 4 + w.n_valid * w.K * 4 \
-            + w.n_valid * (w.d * esz + w.d * 4) + w.N * 13
-        roof = {"bound": "hbm", "kernel": "backward", "achieved": b_bwd / (bwd_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                "unit": "GB/s", "traffic": None}
+    bound, work = kernel_work(w, dominant)
+    if bound == "mfma":
+        peak = PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS
+        roof = {"bound": "mfma", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": peak,
+                "unit": "TFLOP/s"}
     else:
-        f_bwd = flops * 0.75
-        roof = {"bound": "mfma", "kernel": "backward", "achieved": f_bwd / (bwd_ms * 1e-3) / 1e12,
-                "peak": PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS, "unit": "TFLOP/s",
-                "traffic": None}
+        roof = {"bound": "hbm", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["avg_launch_ms"] = bwd_ms
+    roof["traffic"] = measured_traffic(w.name, dominant)
+    roof["avg_launch_ms"] = dom_ms
+    roof["algorithmic_per_launch"] = work
 
     out = {
         "metric": "CE- fwd+bwd positions/sec at 1 GPU",
@@ -157,7 +214,7 @@ def main() -> int:
             "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
             "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
             "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
-            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "dE_zero_fill_ms": memset_ms,
+            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
             "algorithmic_gflop": flops / 1e9, "algorithmic_mbytes": bytes_min / 1e6,
             "whole_step_tflops": flops / (ms_step * 1e-3) / 1e12,
             "whole_step_frac_mfma_peak": flops / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,

@@ -118,6 +118,20 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
  */
 cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement aid for benchmarks and profilers (not part of the method).  While enabled, every kernel launch the library
+ * makes is bracketed by a pair of HIP events on the launch stream.  cce_neg_profile_read waits for the recorded events,
+ * adds the elapsed time per kernel family and returns the number of families written (at most max):
+ *   names     [max][32] char (HOST)   family name, NUL-terminated: "gather_fwd", "gather_bwd", "prep", "tile_fwd",
+ *                                     "fwd_merge", "tile_dh", "dh_merge", "tile_de"
+ *   total_ms  [max] float (HOST)      summed duration since the last read
+ *   launches  [max] int32 (HOST)      launches since the last read
+ * The records are cleared by the read.  Enabling creates HIP events on demand; nothing else in the library allocates.
+ * Not thread-safe; leave it disabled in production.
+ */
+cce_status cce_neg_profile_enable(int32_t enable);
+int32_t cce_neg_profile_read(int32_t max, char *names, float *total_ms, int32_t *launches);
+
 /* Static, NUL-terminated description of a status code. */
 const char *cce_status_string(cce_status status);
 

@@ -23,7 +23,7 @@ CCE_ALGO_AUTO, CCE_ALGO_GATHER, CCE_ALGO_TILE = 0, 1, 2
 
 EXPORTS = (
     "cce_neg_workspace_bytes", "cce_neg_workspace_init", "cce_neg_forward", "cce_neg_backward",
-    "cce_neg_index_status", "cce_status_string",
+    "cce_neg_index_status", "cce_status_string", "cce_neg_profile_enable", "cce_neg_profile_read",
 )
 
 
@@ -63,6 +63,11 @@ def lib() -> ctypes.CDLL:
                                        ctypes.c_size_t, vp]
         L.cce_neg_index_status.restype = ctypes.c_int
         L.cce_neg_index_status.argtypes = [vp, ctypes.c_size_t, vp]
+        L.cce_neg_profile_enable.restype = ctypes.c_int
+        L.cce_neg_profile_enable.argtypes = [ctypes.c_int32]
+        L.cce_neg_profile_read.restype = ctypes.c_int32
+        L.cce_neg_profile_read.argtypes = [ctypes.c_int32, ctypes.c_char_p, ctypes.POINTER(ctypes.c_float),
+                                           ctypes.POINTER(ctypes.c_int32)]
         L.cce_status_string.restype = ctypes.c_char_p
         L.cce_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -130,3 +135,19 @@ def cce_neg_backward(desc: CceDesc, H, E, tgt, neg, mask, lse, grad_loss, dH, dE
 
 def cce_neg_index_status(workspace: torch.Tensor) -> int:
     return int(lib().cce_neg_index_status(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def cce_neg_profile_enable(enable: bool) -> None:
+    lib().cce_neg_profile_enable(1 if enable else 0)
+
+
+def cce_neg_profile_read(max_families: int = 16) -> dict:
+    """{family: (total_ms, launches)} since the last read; waits for the recorded events."""
+    names = ctypes.create_string_buffer(32 * max_families)
+    ms = (ctypes.c_float * max_families)()
+    cnt = (ctypes.c_int32 * max_families)()
+    n = lib().cce_neg_profile_read(max_families, names, ms, cnt)
+    out = {}
+    for i in range(n):
+        out[names.raw[32 * i:32 * (i + 1)].split(b"\0", 1)[0].decode()] = (float(ms[i]), int(cnt[i]))
+    return out

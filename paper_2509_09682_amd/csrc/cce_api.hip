@@ -1,6 +1,9 @@
 // C ABI of the CCE- library: argument checks, workspace layout, dispatch.  See include/cce_neg.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <string.h>
+#include <vector>
+
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
 
@@ -38,7 +41,7 @@ Layout make_layout(const cce_desc *d)
     // Splitting only pays when there are few blocks of stationary rows, which bounds splits * rows, hence the
     // partial buffers, by a constant.
     const int64_t xblocks = (N + 127) / 128;
-    int sx = (xblocks > 0) ? (int)(2048 / xblocks) : 1;
+    int sx = (xblocks > 0 && xblocks <= 320) ? (int)(2048 / xblocks) : 1;  // the launcher never splits above 320 blocks
     const int64_t col_tiles = (n_cols + by - 1) / by;
     if (sx > 16) sx = 16;
     if (sx > col_tiles / 2) sx = (int)(col_tiles / 2);
@@ -172,6 +175,44 @@ PrepArgs make_prep_args(const cce_desc *d, const Layout &L, const int32_t *tgt, 
 
 }  // namespace
 
+// ---- profiling records
+namespace {
+struct ProfRecord {
+    int family;
+    hipEvent_t start, stop;
+};
+bool g_prof_enabled = false;
+std::vector<ProfRecord> g_prof_records;
+std::vector<hipEvent_t> g_prof_pool;
+const char *const kProfNames[PROF_FAMILIES] = {"gather_fwd", "gather_bwd", "prep",     "tile_fwd",
+                                               "fwd_merge",  "tile_dh",    "dh_merge", "tile_de"};
+hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+ProfScope::ProfScope(int family, hipStream_t s) : slot(-1), stream(s)
+{
+    if (!g_prof_enabled) return;
+    ProfRecord r{family, prof_event(), prof_event()};
+    if (!r.start || !r.stop) return;
+    (void)hipEventRecord(r.start, stream);
+    g_prof_records.push_back(r);
+    slot = (int)g_prof_records.size() - 1;
+}
+ProfScope::~ProfScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_prof_records[slot].stop, stream);
+}
+
 hipError_t launch_fill_zero(int32_t *dst, size_t words, hipStream_t stream)
 {
     if (words == 0) return hipSuccess;
@@ -274,6 +315,40 @@ cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *h
         return CCE_ERR_INDEX;
     }
     return CCE_OK;
+}
+
+cce_status cce_neg_profile_enable(int32_t enable)
+{
+    cce::g_prof_enabled = enable != 0;
+    return CCE_OK;
+}
+
+int32_t cce_neg_profile_read(int32_t max, char *names, float *total_ms, int32_t *launches)
+{
+    float sum[cce::PROF_FAMILIES] = {};
+    int32_t cnt[cce::PROF_FAMILIES] = {};
+    for (const cce::ProfRecord &r : cce::g_prof_records) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            sum[r.family] += ms;
+            cnt[r.family] += 1;
+        }
+        cce::g_prof_pool.push_back(r.start);
+        cce::g_prof_pool.push_back(r.stop);
+    }
+    cce::g_prof_records.clear();
+    int32_t n = 0;
+    for (int f = 0; f < cce::PROF_FAMILIES && n < max; ++f) {
+        if (cnt[f] == 0) continue;
+        if (names) {
+            strncpy(names + (size_t)n * 32, cce::kProfNames[f], 31);
+            names[(size_t)n * 32 + 31] = 0;
+        }
+        if (total_ms) total_ms[n] = sum[f];
+        if (launches) launches[n] = cnt[f];
+        ++n;
+    }
+    return n;
 }
 
 const char *cce_status_string(cce_status status)

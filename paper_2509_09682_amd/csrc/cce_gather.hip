@@ -237,6 +237,7 @@ hipError_t launch_pair(bool backward, const Params &p, hipStream_t stream)
     if (p.N == 0) return hipSuccess;
     const dim3 block(kWavesPerBlock * 64);
     const dim3 grid((unsigned)((p.N + kWavesPerBlock - 1) / kWavesPerBlock));
+    ProfScope prof(backward ? PROF_GATHER_BWD : PROF_GATHER_FWD, stream);
     if (backward)
         hipLaunchKernelGGL((bwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
     else

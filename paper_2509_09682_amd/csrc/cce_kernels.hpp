@@ -53,6 +53,16 @@ bool tile_supports_d(int d);
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream);
 hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 
+// Event bracket around a kernel launch while profiling is enabled (see cce_neg_profile_enable); otherwise a no-op.
+enum { PROF_GATHER_FWD = 0, PROF_GATHER_BWD, PROF_PREP, PROF_TILE_FWD, PROF_FWD_MERGE, PROF_TILE_DH, PROF_DH_MERGE,
+       PROF_TILE_DE, PROF_FAMILIES };
+struct ProfScope {
+    ProfScope(int family, hipStream_t stream);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
+
 // Clears `words` 32-bit words at dst with a fill kernel (no memset node).
 hipError_t launch_fill_zero(int32_t *dst, size_t words, hipStream_t stream);
 

@@ -901,6 +901,7 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
         a.de_blocks = blocks;
         blocks += (a.N + kPosChunk - 1) / kPosChunk;
     }
+    ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
@@ -931,6 +932,7 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         else
             e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB_F, DUAL>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
+            ProfScope prof(PROF_FWD_MERGE, stream);
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
             e = hipGetLastError();
         }
@@ -942,6 +944,7 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
             e = launch_tile_kernel<D, MODE_DH, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
+            ProfScope prof(PROF_DH_MERGE, stream);
             hipLaunchKernelGGL((dh_merge_kernel<D>), dim3((unsigned)((a.N + PPB - 1) / PPB)), dim3(256), 0, stream, a);
             e = hipGetLastError();
         }
@@ -962,6 +965,7 @@ bool tile_supports_d(int d) { return d == 64 || d == 128 || d == 256; }
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream)
 {
     if (p.N == 0) return hipSuccess;
+    ProfScope prof(PROF_PREP, stream);
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((p.N + kPrepThreads - 1) / kPrepThreads)), dim3(kPrepThreads), 0,
                        stream, p);
     return hipGetLastError();
