@@ -121,6 +121,34 @@ Params make_params(const cce_desc *d, const void *H, const void *E, const int32_
     return p;
 }
 
+// Workspace of the per-position mode: the correct-item coefficients and the inverted index of the negatives
+// (4 bytes per (position, negative) pair, as large as the `neg` input itself, plus one word per item).
+struct PpLayout {
+    size_t coef, cursor, block_sums, pairs, tmp, part_hist, total;
+};
+PpLayout make_pp_layout(const cce_desc *d)
+{
+    PpLayout L{};
+    const size_t n_pairs = (size_t)d->N * (size_t)d->K;
+    const bool part = invert_partitioned(d->V);
+    const size_t n_hist = part ? (size_t)invert_buckets(d->V) * (size_t)invert_part_blocks(d->N, d->K) + 1 : 0;
+    const size_t scan_n = part ? n_hist : (size_t)d->V;
+    size_t off = kHeaderBytes;
+    L.coef = off;        off += align256((size_t)d->N * 4);
+    L.cursor = off;      off += align256((size_t)d->V * 4);
+    L.block_sums = off;  off += align256(invert_scan_blocks((int64_t)scan_n) * 4);
+    L.pairs = off;       off += align256(n_pairs * 4);
+    L.tmp = off;         off += part ? align256(n_pairs * 8) : 0;
+    L.part_hist = off;   off += align256(n_hist * 4);
+    L.total = off;
+    return L;
+}
+bool use_inverted(const cce_desc *d)
+{
+    // the index holds 32-bit offsets: larger problems keep the atomic row adds of the row-gather pass
+    return d->neg_mode == CCE_NEG_PER_POSITION && d->K > 0 && d->N * (int64_t)d->K < 0x7fffffffLL;
+}
+
 TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const void *E, const int32_t *tgt,
                         const int32_t *neg, const uint8_t *mask, void *workspace)
 {
@@ -184,8 +212,8 @@ struct ProfRecord {
 bool g_prof_enabled = false;
 std::vector<ProfRecord> g_prof_records;
 std::vector<hipEvent_t> g_prof_pool;
-const char *const kProfNames[PROF_FAMILIES] = {"gather_fwd", "gather_bwd", "prep",     "tile_fwd",
-                                               "fwd_merge",  "tile_dh",    "dh_merge", "tile_de"};
+const char *const kProfNames[PROF_FAMILIES] = {"gather_fwd", "gather_bwd", "prep",  "tile_fwd", "fwd_merge",  "tile_dh",
+                                               "dh_merge",   "tile_de",    "index", "item_de",  "pos_scatter"};
 hipEvent_t prof_event()
 {
     if (!g_prof_pool.empty()) {
@@ -228,6 +256,7 @@ size_t cce_neg_workspace_bytes(const cce_desc *desc)
 {
     if (cce::check_desc(desc) != CCE_OK) return 0;
     if (cce::use_tile(desc)) return cce::make_layout(desc).total;
+    if (cce::use_inverted(desc)) return cce::make_pp_layout(desc).total;
     return cce::kHeaderBytes;
 }
 
@@ -297,8 +326,54 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     p.g = grad_loss;
     p.dH = dH;
     p.dE = dE;
-    const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream);
-    return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+    if (!cce::use_inverted(desc)) {
+        const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream);
+        return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+    }
+    // Per-position negatives: the row-gather pass yields dH and the correct-item coefficients; dE of the negatives
+    // comes from the inverted-index pass, dE of the correct items from the aggregated scatter where it exists.
+    const cce::PpLayout L = cce::make_pp_layout(desc);
+    char *ws = static_cast<char *>(workspace);
+    const bool bf16 = desc->in_dtype == CCE_BF16;
+    const bool scatter = bf16 && cce::tile_supports_d(desc->d);
+    p.skip_neg_dE = 1;
+    p.skip_pos_dE = scatter ? 1 : 0;
+    p.coef = reinterpret_cast<float *>(ws + L.coef);
+    if (cce::launch_gather(true, bf16, p, stream) != hipSuccess) return CCE_ERR_HIP;
+    if (scatter) {
+        cce::TileArgs t{};
+        t.H = static_cast<const uint16_t *>(H);
+        t.tgt = tgt;
+        t.pos_mask = mask;
+        t.coef = p.coef;
+        t.dE = dE;
+        t.N = desc->N;
+        t.V = desc->V;
+        t.d = desc->d;
+        t.validate = desc->validate_indices ? 1 : 0;
+        if (cce::launch_pos_scatter(t, stream) != hipSuccess) return CCE_ERR_HIP;
+    }
+    cce::InvertArgs ia{};
+    ia.H = H;
+    ia.E = E;
+    ia.tgt = tgt;
+    ia.neg = neg;
+    ia.mask = mask;
+    ia.lse_in = lse;
+    ia.g = grad_loss;
+    ia.dE = dE;
+    ia.cursor = reinterpret_cast<int32_t *>(ws + L.cursor);
+    ia.block_sums = reinterpret_cast<int32_t *>(ws + L.block_sums);
+    ia.pairs = reinterpret_cast<int32_t *>(ws + L.pairs);
+    ia.tmp = reinterpret_cast<int2 *>(ws + L.tmp);
+    ia.part_hist = reinterpret_cast<int32_t *>(ws + L.part_hist);
+    ia.N = desc->N;
+    ia.V = desc->V;
+    ia.d = desc->d;
+    ia.K = desc->K;
+    ia.collide = desc->mask_target_collisions ? 1 : 0;
+    ia.validate = desc->validate_indices ? 1 : 0;
+    return cce::launch_inverted_dE(bf16, ia, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 
 cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream)

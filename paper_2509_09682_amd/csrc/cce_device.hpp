@@ -24,6 +24,10 @@ struct Params {
     int64_t N, V;
     int32_t d, K;
     int32_t neg_mode, collide, validate, dH_bf16;
+    // backward of the row-gather family when dE of the negatives is produced by the inverted-index pass instead:
+    int32_t skip_neg_dE;    // 1: no dE atomics for negatives
+    int32_t skip_pos_dE;    // 1: no dE atomics for the correct item either (the aggregated scatter adds it)
+    float *coef;            // [N] out: g_i (p+_i - 1), coefficient of the correct item (nullable)
 };
 
 constexpr float kLog2e = 1.4426950408889634f;

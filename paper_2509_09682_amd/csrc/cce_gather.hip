@@ -197,11 +197,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params 
                     const float G = gi * (pj - (cd[u].is_pos ? 1.f : 0.f));
 #pragma unroll
                     for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, e[u][t], acc[t]);
-                    float *row = p.dE + cd[u].id * (int64_t)p.d;
+                    if (cd[u].is_pos && p.coef && c == 0) p.coef[i] = G;
+                    if (cd[u].is_pos ? !p.skip_pos_dE : !p.skip_neg_dE) {
+                        float *row = p.dE + cd[u].id * (int64_t)p.d;
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const int col = c + LPR * t;
-                        if (col < p.d) unsafeAtomicAdd(row + col, G * h2[t]);
+                        for (int t = 0; t < 8; ++t) {
+                            const int col = c + LPR * t;
+                            if (col < p.d) unsafeAtomicAdd(row + col, G * h2[t]);
+                        }
                     }
                 }
             }

@@ -1,0 +1,328 @@
+// dE of per-position negatives through an inverted index (item -> the (position, slot) pairs that sampled it).
+//
+// Alg. 2 updates the classifier gradient with one indexed row add per (position, candidate) pair.  With N*K pairs
+// spread over a large table that is N*K*d floating-point atomics, and this chip retires scattered fp32 atomics at about
+// 1.3 TB/s of payload against 7 TB/s for plain stores.  The same sum can be taken item by item: count the pairs of
+// every item, turn the counts into offsets, file each pair under its item (a counting sort with integer atomics on a
+// V-word table), then let one lane group per item recompute its few scores against hidden states that sit in L2 and
+// add the finished row to dE once, without atomics.  Table rows are read once and written once; no score is stored.
+// The correct items (power-law hot rows) are not part of the index: the aggregated scatter adds them.
+#include "cce_device.hpp"
+#include "cce_kernels.hpp"
+
+namespace cce {
+namespace {
+
+constexpr int kThreads = 256;
+
+// One thread per (position, slot) pair of a valid position whose negative takes part.
+__device__ __forceinline__ bool pair_live(const InvertArgs &a, int64_t pair, int32_t &id)
+{
+    const int64_t i = pair / a.K;
+    if (a.mask && a.mask[i] == 0) return false;
+    id = a.neg[pair];
+    const int32_t ti = a.tgt[i];
+    if (a.validate && (ti < 0 || (int64_t)ti >= a.V || id < 0 || (int64_t)id >= a.V)) return false;  // flagged elsewhere
+    return !(a.collide && id == ti);
+}
+
+// ---- exclusive scan of an int array in two launches: block-local scan + block totals, then every block adds the
+//      totals of the blocks in front of it (read directly: n/4096 values at most)
+constexpr int kScanThreads = 1024;
+constexpr int kScanItems = 4;
+constexpr int kScanChunk = kScanThreads * kScanItems;
+
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *lds, int32_t &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int32_t o = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += o;
+    }
+    __syncthreads();  // lds may still be read from a previous call
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int32_t run = 0;
+        for (int w = 0; w < kScanThreads / 64; ++w) {
+            const int32_t c = lds[w];
+            lds[w] = run;
+            run += c;
+        }
+        lds[kScanThreads / 64] = run;
+    }
+    __syncthreads();
+    total = lds[kScanThreads / 64];
+    return incl - v + lds[wave];
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_local_kernel(int32_t *data, int64_t n, int32_t *block_sums)
+{
+    __shared__ int32_t lds[kScanThreads / 64 + 1];
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+    int32_t v[kScanItems], sum = 0;
+#pragma unroll
+    for (int t = 0; t < kScanItems; ++t) {
+        v[t] = (base + t < n) ? data[base + t] : 0;
+        sum += v[t];
+    }
+    int32_t total;
+    int32_t run = block_exclusive_scan(sum, lds, total);
+#pragma unroll
+    for (int t = 0; t < kScanItems; ++t) {
+        if (base + t < n) data[base + t] = run;
+        run += v[t];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_add_kernel(int32_t *data, int64_t n, const int32_t *block_sums)
+{
+    __shared__ int32_t lds[kScanThreads / 64 + 1];
+    int32_t part = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += kScanThreads) part += block_sums[b];
+    int32_t total;
+    (void)block_exclusive_scan(part, lds, total);
+    const int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+#pragma unroll
+    for (int t = 0; t < kScanItems; ++t)
+        if (base + t < n) data[base + t] += total;
+}
+
+hipError_t launch_scan(int32_t *data, int64_t n, int32_t *block_sums, hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((n + kScanChunk - 1) / kScanChunk);
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(scan_local_kernel, dim3(blocks), dim3(kScanThreads), 0, stream, data, n, block_sums);
+    hipLaunchKernelGGL(scan_add_kernel, dim3(blocks), dim3(kScanThreads), 0, stream, data, n, block_sums);
+    return hipGetLastError();
+}
+
+// ---- fallback index build for huge catalogues: integer atomics on the V-word table (scattered atomics are slow:
+//      about 27 G/s for the count, 10 G/s for the returning ones of the fill)
+__global__ __launch_bounds__(kThreads) void count_kernel(InvertArgs a)
+{
+    const int64_t pair = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (pair >= a.N * a.K) return;
+    int32_t id;
+    if (pair_live(a, pair, id)) atomicAdd(a.cursor + id, 1);
+}
+
+// File every live pair under its item.  Afterwards cursor[v] is the END of item v's segment; it starts where the
+// segment of v-1 ends.
+__global__ __launch_bounds__(kThreads) void fill_kernel(InvertArgs a)
+{
+    const int64_t pair = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (pair >= a.N * a.K) return;
+    int32_t id;
+    if (pair_live(a, pair, id)) {
+        const int32_t slot = atomicAdd(a.cursor + id, 1);
+        a.pairs[slot] = (int32_t)(pair / a.K);  // only the position is needed downstream
+    }
+}
+
+// ---- index build by two-level counting sort without global atomics.
+//  Level 1 partitions the pairs into buckets of kBucketIds consecutive item ids: every block histograms its chunk of
+//  pairs in LDS, the (bucket, block) counts are scanned bucket-major, and the block scatters (id, position) into its
+//  reserved ranges.  Level 2 gives each bucket to one block, which counting-sorts it by id inside LDS and writes the
+//  positions item by item together with the end offset of every item.
+constexpr int kBucketShift = 12;
+constexpr int kBucketIds = 1 << kBucketShift;  // LDS histogram of level 2: 16 KiB
+constexpr int kMaxBuckets = 2048;               // LDS histogram of level 1: 8 KiB
+constexpr int kChunkPairs = 8192;               // pairs per block in level 1
+
+__global__ __launch_bounds__(kThreads) void part_count_kernel(InvertArgs a)
+{
+    __shared__ int32_t hist[kMaxBuckets];
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) hist[b] = 0;
+    __syncthreads();
+    const int64_t p0 = (int64_t)blockIdx.x * kChunkPairs, total = a.N * a.K;
+    for (int u = threadIdx.x; u < kChunkPairs; u += kThreads) {
+        const int64_t pair = p0 + u;
+        int32_t id;
+        if (pair < total && pair_live(a, pair, id)) atomicAdd(&hist[id >> kBucketShift], 1);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) a.part_hist[(int64_t)b * gridDim.x + blockIdx.x] = hist[b];
+}
+
+__global__ __launch_bounds__(kThreads) void part_scatter_kernel(InvertArgs a)
+{
+    __shared__ int32_t cur[kMaxBuckets];
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) cur[b] = a.part_hist[(int64_t)b * gridDim.x + blockIdx.x];
+    __syncthreads();
+    const int64_t p0 = (int64_t)blockIdx.x * kChunkPairs, total = a.N * a.K;
+    for (int u = threadIdx.x; u < kChunkPairs; u += kThreads) {
+        const int64_t pair = p0 + u;
+        int32_t id;
+        if (pair < total && pair_live(a, pair, id)) {
+            const int32_t slot = atomicAdd(&cur[id >> kBucketShift], 1);
+            a.tmp[slot] = make_int2(id, (int32_t)(pair / a.K));
+        }
+    }
+}
+
+__global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
+{
+    __shared__ int32_t hist[kBucketIds];
+    __shared__ int32_t lds[kScanThreads / 64 + 1];
+    const int b = blockIdx.x;
+    const int64_t n_blocks1 = a.n_part_blocks;
+    // the bucket's range in tmp: from the scanned (bucket, block 0) entry to the next bucket's
+    const int32_t rb = a.part_hist[(int64_t)b * n_blocks1];
+    const int32_t re = (b + 1 < a.n_buckets) ? a.part_hist[(int64_t)(b + 1) * n_blocks1] : a.part_total[0];
+    const int64_t id0 = (int64_t)b << kBucketShift;
+    for (int k = threadIdx.x; k < kBucketIds; k += kScanThreads) hist[k] = 0;
+    __syncthreads();
+    for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) atomicAdd(&hist[a.tmp[e].x - (int32_t)id0], 1);
+    __syncthreads();
+    // exclusive scan over the 4096 counts: 4 consecutive ids per thread
+    int32_t v[kBucketIds / kScanThreads], sum = 0;
+#pragma unroll
+    for (int t = 0; t < kBucketIds / kScanThreads; ++t) {
+        v[t] = hist[threadIdx.x * (kBucketIds / kScanThreads) + t];
+        sum += v[t];
+    }
+    int32_t total;
+    int32_t run = block_exclusive_scan(sum, lds, total);
+#pragma unroll
+    for (int t = 0; t < kBucketIds / kScanThreads; ++t) {
+        const int k = threadIdx.x * (kBucketIds / kScanThreads) + t;
+        hist[k] = run;  // start of the item's segment inside the bucket; advanced below while filing
+        run += v[t];
+        if (id0 + k < a.V) a.cursor[id0 + k] = rb + run;  // END of the item's segment
+    }
+    __syncthreads();
+    for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) {
+        const int2 t = a.tmp[e];
+        const int32_t slot = atomicAdd(&hist[t.x - (int32_t)id0], 1);
+        a.pairs[rb + slot] = t.y;
+    }
+}
+
+// One group of LPR lanes per item: e_v stays in registers, the positions that sampled it are walked four at a time.
+template <typename T, int LPR>
+__global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
+{
+    constexpr int GPW = 64 / LPR;  // items per wavefront
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * GPW + lane / LPR;
+    const bool col_ok = c * 8 < a.d;
+    int32_t r = 0, r_end = 0;
+    if (v < a.V) {
+        r = (v == 0) ? 0 : a.cursor[v - 1];
+        r_end = a.cursor[v];
+    }
+    if (!__any(r < r_end)) return;
+    const T *Hp = static_cast<const T *>(a.H);
+    float e[8], acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) e[t] = acc[t] = 0.f;
+    if (r < r_end && col_ok) load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+
+    while (__any(r < r_end)) {
+        int32_t pos[4];
+        float h[4][8], lse[4], g[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            pos[u] = (r + u < r_end) ? a.pairs[r + u] : -1;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) h[u][t] = 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            lse[u] = 0.f;
+            g[u] = 0.f;
+            if (pos[u] >= 0) {
+                if (col_ok) load8(Hp + pos[u] * (int64_t)a.d + c * 8, h[u]);
+                lse[u] = a.lse_in[pos[u]];
+                g[u] = a.g ? a.g[pos[u]] : 1.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float part = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) part = fmaf(h[u][t], e[t], part);
+#pragma unroll
+            for (int off = 1; off < LPR; off <<= 1) part += __shfl_xor(part, off, 64);  // partners share the item
+            const float G = (pos[u] >= 0) ? g[u] * fast_exp(part - lse[u]) : 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, h[u][t], acc[t]);
+        }
+        r += 4;
+    }
+    // the row belongs to this lane group alone: plain read-modify-write
+    if (v < a.V && col_ok && ((v == 0 ? 0 : a.cursor[v - 1]) < a.cursor[v])) {
+        float4 *row = reinterpret_cast<float4 *>(a.dE + v * (int64_t)a.d + c * 8);
+        float4 x = row[0], y = row[1];
+        x.x += acc[0]; x.y += acc[1]; x.z += acc[2]; x.w += acc[3];
+        y.x += acc[4]; y.y += acc[5]; y.z += acc[6]; y.w += acc[7];
+        row[0] = x;
+        row[1] = y;
+    }
+}
+
+template <typename T, int LPR>
+hipError_t launch_item_dE(const InvertArgs &a, hipStream_t stream)
+{
+    constexpr int items_per_block = (kThreads / 64) * (64 / LPR);
+    ProfScope prof(PROF_ITEM_DE, stream);
+    hipLaunchKernelGGL((item_dE_kernel<T, LPR>), dim3((unsigned)((a.V + items_per_block - 1) / items_per_block)),
+                       dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_item_dE_by_width(const InvertArgs &a, hipStream_t stream)
+{
+    const int chunks = (a.d + 7) / 8;
+    if (chunks <= 2) return launch_item_dE<T, 2>(a, stream);
+    if (chunks <= 4) return launch_item_dE<T, 4>(a, stream);
+    if (chunks <= 8) return launch_item_dE<T, 8>(a, stream);
+    if (chunks <= 16) return launch_item_dE<T, 16>(a, stream);
+    if (chunks <= 32) return launch_item_dE<T, 32>(a, stream);
+    return launch_item_dE<T, 64>(a, stream);
+}
+
+}  // namespace
+
+size_t invert_scan_blocks(int64_t n) { return (size_t)((n + kScanChunk - 1) / kScanChunk); }
+int64_t invert_part_blocks(int64_t N, int64_t K) { return (N * K + kChunkPairs - 1) / kChunkPairs; }
+int64_t invert_buckets(int64_t V) { return (V + kBucketIds - 1) / kBucketIds; }
+bool invert_partitioned(int64_t V) { return invert_buckets(V) <= kMaxBuckets; }
+
+hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, hipStream_t stream)
+{
+    InvertArgs a = a_in;
+    if (a.N == 0 || a.K == 0) return hipSuccess;
+    const int64_t pairs = a.N * a.K;
+    hipError_t e;
+    {
+        ProfScope prof(PROF_INDEX, stream);
+        if (invert_partitioned(a.V)) {
+            a.n_buckets = (int32_t)invert_buckets(a.V);
+            a.n_part_blocks = invert_part_blocks(a.N, a.K);
+            const int64_t n_hist = (int64_t)a.n_buckets * a.n_part_blocks;
+            a.part_total = a.part_hist + n_hist;  // one extra word: scanning n_hist + 1 entries leaves the grand total there
+            hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+            if ((e = launch_fill_zero(a.part_total, 1, stream)) != hipSuccess) return e;
+            if ((e = launch_scan(a.part_hist, n_hist + 1, a.block_sums, stream)) != hipSuccess) return e;
+            hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+            hipLaunchKernelGGL(bucket_sort_kernel, dim3((unsigned)a.n_buckets), dim3(kScanThreads), 0, stream, a);
+        } else {
+            const unsigned pair_blocks = (unsigned)((pairs + kThreads - 1) / kThreads);
+            if ((e = launch_fill_zero(a.cursor, (size_t)a.V, stream)) != hipSuccess) return e;
+            hipLaunchKernelGGL(count_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
+            if ((e = launch_scan(a.cursor, a.V, a.block_sums, stream)) != hipSuccess) return e;
+            hipLaunchKernelGGL(fill_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return bf16 ? launch_item_dE_by_width<uint16_t>(a, stream) : launch_item_dE_by_width<float>(a, stream);
+}
+
+}  // namespace cce

@@ -34,6 +34,7 @@ struct TileArgs {
     const int32_t *idx;          // compacted position -> position row; nullptr = identity
     const int32_t *n_valid_ptr;  // device count of valid positions; nullptr = N
     const int32_t *cnt;          // target multiplicity per position; nullptr = 0
+    const uint8_t *pos_mask;     // stand-alone scatter without compaction: padding mask (nullable)
     const float *lse_in;
     const float *g;
     float *loss, *lse;
@@ -49,13 +50,41 @@ struct TileArgs {
 
 enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items
 
+// ---- inverted-index dE of per-position negatives
+struct InvertArgs {
+    const void *H;
+    const void *E;
+    const int32_t *tgt;
+    const int32_t *neg;      // [N,K]
+    const uint8_t *mask;     // nullable
+    const float *lse_in;
+    const float *g;          // nullable
+    float *dE;
+    int32_t *cursor;         // [V] workspace: counts -> segment starts -> segment ends
+    int32_t *block_sums;     // [invert_scan_blocks(V)] workspace
+    int32_t *pairs;          // [N*K] workspace: positions filed under their item
+    int2 *tmp;               // [N*K] workspace: (id, position) partitioned by bucket
+    int32_t *part_hist;      // [n_buckets * n_part_blocks + 1] workspace: (bucket, block) counts -> offsets
+    int32_t *part_total;     // = part_hist + n_buckets * n_part_blocks (set by the launcher)
+    int64_t N, V, n_part_blocks;
+    int32_t d, K, collide, validate, n_buckets;
+};
+size_t invert_scan_blocks(int64_t n);          // blocks of the scan over n words (size of block_sums)
+int64_t invert_part_blocks(int64_t N, int64_t K);
+int64_t invert_buckets(int64_t V);
+bool invert_partitioned(int64_t V);            // false: catalogue too large for the LDS bucket histogram, atomics are used
+hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a, hipStream_t stream);
+
+// Aggregated scatter of the correct items on its own (bf16 inputs, d in {64,128,256}): dE[tgt_i] += coef_i * H_i.
+hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream);
+
 bool tile_supports_d(int d);
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream);
 hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 
 // Event bracket around a kernel launch while profiling is enabled (see cce_neg_profile_enable); otherwise a no-op.
 enum { PROF_GATHER_FWD = 0, PROF_GATHER_BWD, PROF_PREP, PROF_TILE_FWD, PROF_FWD_MERGE, PROF_TILE_DH, PROF_DH_MERGE,
-       PROF_TILE_DE, PROF_FAMILIES };
+       PROF_TILE_DE, PROF_INDEX, PROF_ITEM_DE, PROF_POS_SCATTER, PROF_FAMILIES };
 struct ProfScope {
     ProfScope(int family, hipStream_t stream);
     ~ProfScope();

@@ -117,7 +117,10 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
         uint64_t key = ~0ull;  // padding sorts last
         if (base + tid < n_pos) {
             const int64_t row = pos_row(a, base + tid);
-            key = ((uint64_t)(uint32_t)a.tgt[row] << 32) | (uint32_t)row;
+            if (!a.pos_mask || a.pos_mask[row] != 0) {  // ids of padded positions are never read
+                const int32_t ti = a.tgt[row];
+                if (!a.validate || (ti >= 0 && (int64_t)ti < a.V)) key = ((uint64_t)(uint32_t)ti << 32) | (uint32_t)row;
+            }
         }
         keys[tid] = key;
     }
@@ -960,7 +963,28 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
 
 }  // namespace
 
+template <int D>
+__global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
+{
+    __shared__ uint64_t keys[kPosChunk];
+    pos_scatter_block<D>(a, blockIdx.x, keys);
+}
+
 bool tile_supports_d(int d) { return d == 64 || d == 128 || d == 256; }
+
+hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream)
+{
+    if (a.N == 0) return hipSuccess;
+    const dim3 grid((unsigned)((a.N + kPosChunk - 1) / kPosChunk)), block(kPosChunk);
+    ProfScope prof(PROF_POS_SCATTER, stream);
+    switch (a.d) {
+    case 64: hipLaunchKernelGGL((pos_scatter_kernel<64>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((pos_scatter_kernel<128>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((pos_scatter_kernel<256>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
 
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream)
 {
