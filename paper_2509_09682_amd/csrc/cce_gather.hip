@@ -139,7 +139,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params 
     }
 }
 
-template <typename T, int LPR>
+// ATOMIC_DE = false: dE comes from other passes (inverted index, aggregated scatter); this pass yields dH and the
+// correct-item coefficients only.
+template <typename T, int LPR, bool ATOMIC_DE>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params p)
 {
     constexpr int RPI = 64 / LPR;
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params 
         for (int t = 0; t < 8; ++t) {
             h[t] = 0.f;
             const int col = c + LPR * t;
-            h2[t] = (col < p.d) ? load1(Hp + i * (int64_t)p.d + col) : 0.f;
+            h2[t] = (ATOMIC_DE && col < p.d) ? load1(Hp + i * (int64_t)p.d + col) : 0.f;
         }
         if (col_ok) load8(Hp + i * (int64_t)p.d + c * 8, h);
         const float lse = p.lse_in[i];
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params 
 #pragma unroll
                     for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, e[u][t], acc[t]);
                     if (cd[u].is_pos && p.coef && c == 0) p.coef[i] = G;
-                    if (cd[u].is_pos ? !p.skip_pos_dE : !p.skip_neg_dE) {
+                    if (ATOMIC_DE && (cd[u].is_pos ? !p.skip_pos_dE : !p.skip_neg_dE)) {
                         float *row = p.dE + cd[u].id * (int64_t)p.d;
 #pragma unroll
                         for (int t = 0; t < 8; ++t) {
@@ -241,8 +243,10 @@ hipError_t launch_pair(bool backward, const Params &p, hipStream_t stream)
     const dim3 block(kWavesPerBlock * 64);
     const dim3 grid((unsigned)((p.N + kWavesPerBlock - 1) / kWavesPerBlock));
     ProfScope prof(backward ? PROF_GATHER_BWD : PROF_GATHER_FWD, stream);
-    if (backward)
-        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
+    if (backward && p.skip_neg_dE && p.skip_pos_dE)
+        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, false>), grid, block, 0, stream, p);
+    else if (backward)
+        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, true>), grid, block, 0, stream, p);
     else
         hipLaunchKernelGGL((fwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
     return hipGetLastError();

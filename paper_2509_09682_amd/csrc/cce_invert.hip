@@ -128,8 +128,8 @@ __global__ __launch_bounds__(kThreads) void fill_kernel(InvertArgs a)
 //  pairs in LDS, the (bucket, block) counts are scanned bucket-major, and the block scatters (id, position) into its
 //  reserved ranges.  Level 2 gives each bucket to one block, which counting-sorts it by id inside LDS and writes the
 //  positions item by item together with the end offset of every item.
-constexpr int kBucketShift = 12;
-constexpr int kBucketIds = 1 << kBucketShift;  // LDS histogram of level 2: 16 KiB
+constexpr int kBucketShift = 11;
+constexpr int kBucketIds = 1 << kBucketShift;  // LDS histogram of level 2: 8 KiB
 constexpr int kMaxBuckets = 2048;               // LDS histogram of level 1: 8 KiB
 constexpr int kChunkPairs = 8192;               // pairs per block in level 1
 
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
     __syncthreads();
     for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) atomicAdd(&hist[a.tmp[e].x - (int32_t)id0], 1);
     __syncthreads();
-    // exclusive scan over the 4096 counts: 4 consecutive ids per thread
+    // exclusive scan over the counts: consecutive ids per thread
     int32_t v[kBucketIds / kScanThreads], sum = 0;
 #pragma unroll
     for (int t = 0; t < kBucketIds / kScanThreads; ++t) {
@@ -221,7 +221,15 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
     float e[8], acc[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) e[t] = acc[t] = 0.f;
-    if (r < r_end && col_ok) load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+    // the item row and the dE row it will be added to are requested together, before the walk over the positions
+    const bool mine = r < r_end && col_ok;
+    float4 *row = reinterpret_cast<float4 *>(a.dE + (mine ? v : 0) * (int64_t)a.d + c * 8);
+    float4 dx = make_float4(0.f, 0.f, 0.f, 0.f), dy = dx;
+    if (mine) {
+        load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+        dx = row[0];
+        dy = row[1];
+    }
 
     while (__any(r < r_end)) {
         int32_t pos[4];
@@ -256,13 +264,11 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
         r += 4;
     }
     // the row belongs to this lane group alone: plain read-modify-write
-    if (v < a.V && col_ok && ((v == 0 ? 0 : a.cursor[v - 1]) < a.cursor[v])) {
-        float4 *row = reinterpret_cast<float4 *>(a.dE + v * (int64_t)a.d + c * 8);
-        float4 x = row[0], y = row[1];
-        x.x += acc[0]; x.y += acc[1]; x.z += acc[2]; x.w += acc[3];
-        y.x += acc[4]; y.y += acc[5]; y.z += acc[6]; y.w += acc[7];
-        row[0] = x;
-        row[1] = y;
+    if (mine) {
+        dx.x += acc[0]; dx.y += acc[1]; dx.z += acc[2]; dx.w += acc[3];
+        dy.x += acc[4]; dy.y += acc[5]; dy.z += acc[6]; dy.w += acc[7];
+        row[0] = dx;
+        row[1] = dy;
     }
 }
 

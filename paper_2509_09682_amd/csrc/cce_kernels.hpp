@@ -44,7 +44,7 @@ struct TileArgs {
     float *part_m, *part_s;      // [splits, N] partial max / sum of split forward runs
     float *part_dH;              // [splits, N, d] partial dH of split runs
     int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode
-    int64_t de_blocks;           // dE launch: blocks [0, de_blocks) run the dE pass, the rest scatter the correct items
+    int64_t pos_blocks;          // dE launch: blocks [0, pos_blocks) scatter the correct items, the rest run the dE pass
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
 };
 

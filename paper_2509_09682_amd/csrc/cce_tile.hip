@@ -19,8 +19,6 @@
 // target: the dense tile counts those c_i copies, the definition wants the target exactly once, so
 //   sum_live exp(o) = sum_k exp(o_ik) + w_i exp(o+_i),   coefficient of the correct item = g_i (w_i p+_i - 1).
 // With collision masking off w_i = 1; in full-catalogue mode the target is already one of the columns and w_i = 0.
-#include <stdlib.h>
-
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
 
@@ -226,16 +224,17 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     const int lo = lane & 31;
     const int hi = lane >> 5;
 
-    if (MODE == MODE_DE && (int64_t)blockIdx.x >= a.de_blocks) {  // trailing blocks: scatter of the correct items
+    if (MODE == MODE_DE && (int64_t)blockIdx.x < a.pos_blocks) {  // leading blocks: scatter of the correct items
         static_assert(NW * 64 == kPosChunk, "the scatter role expects 256 threads");
-        pos_scatter_block<D>(a, (int64_t)blockIdx.x - a.de_blocks, reinterpret_cast<uint64_t *>(tileA));
+        pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(tileA));
         return;
     }
+    const int64_t bid = (MODE == MODE_DE) ? (int64_t)blockIdx.x - a.pos_blocks : (int64_t)blockIdx.x;
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t n_x = (MODE == MODE_DE) ? a.n_cols : n_pos;
     const int64_t n_y = (MODE == MODE_DE) ? n_pos : a.n_cols;
-    const int split = blockIdx.x % a.splits;
-    const int64_t xb = blockIdx.x / a.splits;
+    const int split = (int)(bid % a.splits);
+    const int64_t xb = bid / a.splits;
     if (xb * XPB >= n_x) return;  // whole block past the end (the grid is sized for the unmasked N)
 
     const uint16_t *Xbase = (MODE == MODE_DE) ? a.E : a.H;
@@ -282,8 +281,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     // ---- streamed tiles: global memory -> LDS without passing through registers.  One instruction moves 1 KiB:
     //      lane l of the wavefront writes 16 bytes at (wave-uniform base) + 16 l, so the lane that owns LDS slot
     //      (row r, physical chunk pc) fetches the logical chunk pc ^ swz(r) of that row.
-    float stage_c = 0.f;
-    uint32_t stage_s = 0;
+    float stage_g = 1.f, stage_l = 0.f;
+    bool stage_ok = false;
     // Row numbers of the streamed rows are fetched one tile ahead of the rows themselves, so that the address of a
     // direct-to-LDS load never waits for an index load issued in the same step.
     int64_t next_row[LPW];
@@ -314,22 +313,18 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
             const uint16_t *src = Ybase + next_row[i] * D + c * 8;
             __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst_tile + inst * 512), 16, 0, 0);
         }
-        if (MODE == MODE_DE && tid < BY) {
-            stage_c = -INFINITY;
-            stage_s = 0;
-            if (y0 + tid < n_y) {
-                const float g = a.g ? a.g[next_crow] : 1.f;
-                // g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|)
-                stage_c = -a.lse_in[next_crow] * kLog2e + __builtin_amdgcn_logf(fabsf(g));
-                stage_s = __float_as_uint(g) & 0x80000000u;
-            }
+        if (MODE == MODE_DE && tid < BY) {  // requested here, turned into constants only after the current tile
+            stage_ok = y0 + tid < n_y;
+            stage_g = (stage_ok && a.g) ? a.g[next_crow] : 1.f;
+            stage_l = stage_ok ? a.lse_in[next_crow] : 0.f;
         }
         if (t + 1 < t_end) fetch_rows(t + 1);
     };
     auto publish_consts = [&](float *yc, uint32_t *ys) {
         if (MODE == MODE_DE && tid < BY) {
-            yc[tid] = stage_c;
-            ys[tid] = stage_s;
+            // g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|); rows past the end get 2^-inf = 0
+            yc[tid] = stage_ok ? -stage_l * kLog2e + __builtin_amdgcn_logf(fabsf(stage_g)) : -INFINITY;
+            ys[tid] = __float_as_uint(stage_g) & 0x80000000u;
         }
     };
 
@@ -897,12 +892,17 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
     const int64_t xblocks = (n_x + XPB - 1) / XPB;
     if (xblocks == 0) return hipSuccess;
     static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>, NW * 64);
-    // the dE pass pays for every split with a full set of atomics on its rows: stay within about one block per CU
-    a.splits = (MODE == MODE_DE) ? pick_splits(xblocks, a.splits, slots < 320 ? slots : 320) : pick_splits(xblocks, a.splits, slots);
-    int64_t blocks = xblocks * a.splits;
     if (MODE == MODE_DE) {
-        a.de_blocks = blocks;
-        blocks += (a.N + kPosChunk - 1) / kPosChunk;
+        // every split of the position range pays n_cols * d atomics: keep them below about a quarter of the matrix
+        // time of the pass (4 n_cols d N flop at ~1 PFLOP/s against ~300 G atomics/s) => splits <= 3e-4 N
+        const int cap = (int)(a.N * 5e-4) < 8 ? 8 : (int)(a.N * 5e-4);
+        if (a.splits > cap) a.splits = cap;
+    }
+    a.splits = pick_splits(xblocks, a.splits, slots);
+    int64_t blocks = xblocks * a.splits;
+    if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
+        a.pos_blocks = (a.N + kPosChunk - 1) / kPosChunk;
+        blocks += a.pos_blocks;
     }
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
