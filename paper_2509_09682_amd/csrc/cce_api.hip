@@ -26,7 +26,7 @@ bool use_tile(const cce_desc *d) { return d->algo != CCE_ALGO_GATHER && tile_eli
 // Workspace layout of the matrix-core path.  Split factors depend on the descriptor only, so that the size query and
 // the launches agree.
 struct Layout {
-    size_t idx, cnt, coef, part_m, part_s, part_dH, total;
+    size_t idx, cnt, coef, de_const, part_m, part_s, part_dH, total;
     int splits_x;   // forward / dH passes: candidate range split over this many blocks per position block
     int splits_de;  // dE pass: position range split
 };
@@ -59,6 +59,7 @@ Layout make_layout(const cce_desc *d)
     L.idx = off;      off += align256((size_t)N * 4);
     L.cnt = off;      off += align256((size_t)N * 4);
     L.coef = off;     off += align256((size_t)N * 4);
+    L.de_const = off; off += align256((size_t)N * 8);
     L.part_m = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
     L.part_s = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
     L.part_dH = off;  off += (sx > 1) ? align256((size_t)sx * N * d->d * 4) : 0;
@@ -165,6 +166,7 @@ TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const
     a.n_valid_ptr = compact ? header + kHdrNValid : nullptr;
     a.cnt = (shared && d->mask_target_collisions) ? reinterpret_cast<const int32_t *>(ws + L.cnt) : nullptr;
     a.coef = reinterpret_cast<float *>(ws + L.coef);
+    a.de_const = reinterpret_cast<uint32_t *>(ws + L.de_const);
     a.part_m = reinterpret_cast<float *>(ws + L.part_m);
     a.part_s = reinterpret_cast<float *>(ws + L.part_s);
     a.part_dH = reinterpret_cast<float *>(ws + L.part_dH);

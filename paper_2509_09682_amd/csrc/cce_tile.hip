@@ -86,10 +86,19 @@ __device__ __forceinline__ float half_row_dot(const uint4 (&xr)[D / 16], const u
     return s;
 }
 
-// XOR pattern of the 16-byte chunk position inside an unpadded LDS row.  It takes 8 different values on 8 consecutive
-// rows (conflict-free 128-bit operand reads, one row per lane) and its upper two bits differ on 4 consecutive rows
-// (conflict-free transpose reads, which fetch 32 bytes from each of 4 rows).
-__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// XOR pattern of the 16-byte chunk position inside an unpadded LDS row of CPR chunks.  LDS serves 256 bytes per clock:
+// a 128-bit read is done 16 lanes at a time, a 64-bit transpose read 32 lanes at a time, and either runs at full rate
+// only if those lanes touch 256 distinct bytes modulo 256.
+//   128-bit operand reads: 16 consecutive rows, one chunk each -> (row * CPR + chunk) mod 16 must take 16 values;
+//   transpose reads: 4 consecutive rows x 4 consecutive chunks -> the 16 (row, chunk) slots must differ modulo 16.
+// Rows of 8 chunks alternate between the two halves of a 256-byte line, so 3 swizzle bits do; longer rows all start
+// on the same bank and need 4.  (Measured: 209-214 bytes per clock for both read kinds, against 125 with a pattern
+// that is only distinct over 8 rows.)
+template <int CPR>
+__device__ __forceinline__ int swz(int row)
+{
+    return CPR == 8 ? ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
+}
 
 typedef const void __attribute__((address_space(1))) *global_cptr;
 typedef void __attribute__((address_space(3))) *lds_ptr;
@@ -191,32 +200,84 @@ __device__ __forceinline__ float max3(float x, float y, float z)
     return r;
 }
 
+// Waits until at most K of the wavefront's vector-memory operations are outstanding (they complete in issue order).
+template <int K>
+__device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(K) : "memory");
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(), which would wait for every load in flight: the
+// wavefront's own LDS reads are drained, loads into other buffers keep flying.  Visibility of landed direct-to-LDS
+// data is the caller's business (wait_all_but before the barrier).
+__device__ __forceinline__ void barrier_keep_loads()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Waits until all but the youngest `groups` load groups of the wavefront have landed.  A group is BASE + extras
+// direct-to-LDS instructions, extras in {0, 1, 2}; groups beyond 2 are treated as 2 (waiting for more is always safe).
+template <int BASE>
+__device__ __forceinline__ void wait_all_but(int groups, int extras)
+{
+    if (groups <= 0) {
+        wait_vm<0>();
+    } else if (groups == 1) {
+        if (extras == 0) wait_vm<BASE>();
+        else if (extras == 1) wait_vm<BASE + 1>();
+        else wait_vm<BASE + 2>();
+    } else {
+        if (extras == 0) wait_vm<2 * BASE>();
+        else if (extras == 1) wait_vm<2 * BASE + 2>();
+        else wait_vm<2 * BASE + 4>();
+    }
+}
+
 // D: hidden size.  BY: streamed rows per LDS tile.  NW: wavefronts per block.  XG: groups of 32 stationary rows per
 // wavefront (XG = 2 reads every streamed operand from LDS once for two matrix instructions).  MINB: blocks per
-// compute unit the register budget is sized for.
-template <int D, int MODE, int BY, int NW, int XG, int MINB, bool DUAL>
+// compute unit the register budget is sized for.  NBUF: LDS tile buffers in the ring (2..4: separate arrays, main loop
+// unrolled NBUF times, NBUF - 1 tiles in flight; 0: two buffers in one array and a single copy of the loop body).
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF>
 __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 {
-    constexpr bool SWP = (D <= 128);       // registers allow a second score tile in flight up to d = 128
+    constexpr bool SWP = (BY % 64 == 0);   // the pipelined sub-tile loop alternates between two register sets
     constexpr int KK = D / 16;             // k-steps of the score product
     constexpr int MB = D / 32;             // 32-row output blocks of the second product
     constexpr int CPR = D / 8;             // 16-byte chunks per row
+    constexpr int SM = (CPR == 8) ? 7 : 15;  // chunk-index bits that the LDS swizzle permutes
+    constexpr int NA = (KK < (SM + 1) / 2) ? KK : (SM + 1) / 2;  // distinct swizzled offsets of the operand reads
+    constexpr int NT = (MB < (SM + 1) / 4) ? MB : (SM + 1) / 4;  // ... and of the transpose reads
     constexpr int XPB = NW * XG * 32;      // stationary rows per block
     constexpr int TILE = BY * D;           // elements per LDS tile
     constexpr int LOADS = BY * CPR / 64;   // 1-KiB direct-to-LDS load instructions per tile
     static_assert(LOADS % NW == 0, "tile loads must split evenly over the wavefronts");
     constexpr int LPW = LOADS / NW;
-    static_assert(NW % 2 == 0 && TILE * 2 >= (NW / 2) * 32 * 33 * 4, "tile buffers too small for the dE transpose");
+    static_assert(NBUF == 0 || (NBUF >= 2 && NBUF <= 4), "ring of 2 to 4 buffers, or 0 for the rolled form");
+    constexpr int PF = (NBUF == 0) ? 1 : NBUF - 1;  // prefetch distance in tiles
+    constexpr int NB = (NBUF == 0) ? 2 : NBUF;
+    // A buffer holds the rows of a tile, (dE) the 2 x BY coefficient constants of its rows, and the row numbers of the
+    // tile PF places further on, which ride along so that no load in the main loop returns into registers: the
+    // outstanding-load count of a wavefront is then made of whole groups of known size.
+    constexpr int IDS = (BY < 64) ? 64 : BY;                 // row numbers are fetched 64 at a time
+    constexpr int CONSTS = (MODE == MODE_DE) ? 2 * BY : 0;   // 32-bit words
+    constexpr int OFF_C = TILE, OFF_I = TILE + 2 * CONSTS;   // offsets in 16-bit elements
+    constexpr int BUF = ((TILE + 2 * CONSTS + 2 * IDS + 511) / 512) * 512;
+    constexpr int CI = (2 * BY / 64 < 1) ? 1 : 2 * BY / 64;  // 256-byte load instructions that fetch the constants
+    constexpr int NI = IDS / 64;                             // ... and the row numbers
+    static_assert(CI <= NW && NI <= NW, "every wavefront issues exactly one instruction of each kind");
+    static_assert(NW % 2 == 0 && TILE * 2 >= (NW / 2) * 32 * 33 * 4 + XPB * 8, "tile buffers too small for the dE epilogue");
 
-    // Two tile buffers.  As separate arrays (DUAL, main loop unrolled twice) the compiler knows that operand reads of
-    // one buffer cannot touch the other and does not wait for the loads in flight into it; the single-array form
-    // keeps one copy of the loop body where registers are short, and leans on the second block of the compute unit.
-    __shared__ __attribute__((aligned(1024))) uint16_t tileA[DUAL ? TILE : 2 * TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t tileB_[DUAL ? TILE : 8];
-    uint16_t *const tileB = DUAL ? tileB_ : tileA + TILE;
-    __shared__ __attribute__((aligned(16))) float ycA[BY], ycB[BY];
-    __shared__ __attribute__((aligned(16))) uint32_t ysA[BY], ysB[BY];
-    __shared__ int64_t xrow_s[XPB];
+    // Separate arrays let the compiler see that operand reads of one buffer cannot touch the buffers that loads are
+    // in flight into, so it does not wait for them; the single-array form keeps one copy of the loop body where
+    // registers are short, and leans on the second block of the compute unit.
+    __shared__ __attribute__((aligned(1024))) uint16_t buf0[NBUF == 0 ? 2 * BUF : BUF];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf1[NBUF >= 2 ? BUF : 8];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf2[NBUF >= 3 ? BUF : 8];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf3[NBUF >= 4 ? BUF : 8];
+    auto buf_at = [&](int i) -> uint16_t * {
+        if (NBUF == 0) return buf0 + (i & 1) * BUF;
+        return i == 0 ? buf0 : (i == 1 ? buf1 : (i == 2 ? buf2 : buf3));
+    };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -226,7 +287,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 
     if (MODE == MODE_DE && (int64_t)blockIdx.x < a.pos_blocks) {  // leading blocks: scatter of the correct items
         static_assert(NW * 64 == kPosChunk, "the scatter role expects 256 threads");
-        pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(tileA));
+        pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(buf0));
         return;
     }
     const int64_t bid = (MODE == MODE_DE) ? (int64_t)blockIdx.x - a.pos_blocks : (int64_t)blockIdx.x;
@@ -254,7 +315,16 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) xr[g][kk] = *reinterpret_cast<const uint4 *>(xp + kk * 16 + hi * 8);
         cx[g] = 0.f;
-        if (MODE == MODE_DH) cx[g] = -a.lse_in[xrow[g]] * kLog2e;
+        if (MODE == MODE_DH) {
+            cx[g] = -a.lse_in[xrow[g]] * kLog2e;
+            // The dE pass wants g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|) for every position it
+            // streams: offset and sign are filed here under the compacted index, where that pass finds them in order.
+            if (split == 0 && hi == 0 && x_ok[g]) {
+                const float gg = a.g ? a.g[xrow[g]] : 1.f;
+                a.de_const[x] = __float_as_uint(cx[g] + __builtin_amdgcn_logf(fabsf(gg)));
+                a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
+            }
+        }
     }
 
     // ---- range of streamed tiles of this split
@@ -281,90 +351,110 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     // ---- streamed tiles: global memory -> LDS without passing through registers.  One instruction moves 1 KiB:
     //      lane l of the wavefront writes 16 bytes at (wave-uniform base) + 16 l, so the lane that owns LDS slot
     //      (row r, physical chunk pc) fetches the logical chunk pc ^ swz(r) of that row.
-    float stage_g = 1.f, stage_l = 0.f;
-    bool stage_ok = false;
-    // Row numbers of the streamed rows are fetched one tile ahead of the rows themselves, so that the address of a
-    // direct-to-LDS load never waits for an index load issued in the same step.
-    int64_t next_row[LPW];
-    int64_t next_crow = 0;  // DE: position row whose constants thread tid publishes
-    auto fetch_rows = [&](int64_t t) {
-        const int64_t y0 = t * BY;
+    const int32_t *const ind = (MODE == MODE_DE) ? a.idx : a.neg;  // streamed index -> row; nullptr = identity
+    const int group_extras = (MODE == MODE_DE ? 1 : 0) + (ind ? 1 : 0);  // instructions per group beyond LPW
+    auto checked_row = [&](int32_t id) -> int32_t {
+        if (MODE != MODE_DE && a.validate && (id < 0 || (int64_t)id >= a.V)) id = 0;  // flagged by the preparation kernel
+        return id;
+    };
+    // Row numbers of a tile's rows, as each lane needs them for its LPW load instructions: straight from global memory
+    // (prologue), or from the copy that an earlier load group left in LDS.
+    auto rows_from_global = [&](int64_t t, int32_t (&rows)[LPW]) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int r = ((wave + i * NW) * 64 + lane) / CPR;
-            int64_t y = y0 + r;
+            int64_t y = t * BY + r;
             if (y >= n_y) y = n_y - 1;  // rows past the end repeat the last row (finite data); they are masked below
-            next_row[i] = (MODE == MODE_DE) ? pos_row(a, y) : item_row(a, y);
-        }
-        if (MODE == MODE_DE && tid < BY) {
-            int64_t y = y0 + tid;
-            if (y >= n_y) y = n_y - 1;
-            next_crow = pos_row(a, y);
+            rows[i] = ind ? checked_row(ind[y]) : (int32_t)y;
         }
     };
-    auto issue_tile = [&](int64_t t, uint16_t *dst_tile) {
-        const int64_t y0 = t * BY;
+    auto rows_from_lds = [&](int64_t t, const uint16_t *holder, int32_t (&rows)[LPW]) {
+        const int32_t *ids = reinterpret_cast<const int32_t *>(holder + OFF_I);
+        if (ind) {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) rows[i] = checked_row(ids[((wave + i * NW) * 64 + lane) / CPR]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const int64_t y = t * BY + ((wave + i * NW) * 64 + lane) / CPR;
+                rows[i] = (int32_t)(y < n_y ? y : n_y - 1);
+            }
+        }
+    };
+    // One load group: the rows of tile t, (dE) the constants of its rows, and the row numbers of tile t + PF.
+    auto issue_group = [&](int64_t t, const int32_t (&rows)[LPW], uint16_t *dst) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int inst = wave + i * NW;
             const int L = inst * 64 + lane;
             const int r = L / CPR, pc = L % CPR;
-            const int c = (pc & ~7) | ((pc & 7) ^ swz(r));
-            const uint16_t *src = Ybase + next_row[i] * D + c * 8;
-            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst_tile + inst * 512), 16, 0, 0);
+            const int c = (pc & ~SM) | ((pc & SM) ^ swz<CPR>(r));
+            const uint16_t *src = Ybase + (int64_t)rows[i] * D + c * 8;
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + inst * 512), 16, 0, 0);
         }
-        if (MODE == MODE_DE && tid < BY) {  // requested here, turned into constants only after the current tile
-            stage_ok = y0 + tid < n_y;
-            stage_g = (stage_ok && a.g) ? a.g[next_crow] : 1.f;
-            stage_l = stage_ok ? a.lse_in[next_crow] : 0.f;
+        if (MODE == MODE_DE) {  // wavefronts beyond CI repeat a load (same data, same place): group sizes stay uniform
+            const int inst = wave % CI;
+            const int e = inst * 64 + lane;
+            int64_t y = t * BY + (e % BY);
+            if (y >= n_y) y = n_y - 1;
+            const uint32_t *src = a.de_const + (int64_t)(e / BY) * a.N + y;
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + OFF_C + inst * 128), 4, 0, 0);
         }
-        if (t + 1 < t_end) fetch_rows(t + 1);
-    };
-    auto publish_consts = [&](float *yc, uint32_t *ys) {
-        if (MODE == MODE_DE && tid < BY) {
-            // g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|); rows past the end get 2^-inf = 0
-            yc[tid] = stage_ok ? -stage_l * kLog2e + __builtin_amdgcn_logf(fabsf(stage_g)) : -INFINITY;
-            ys[tid] = __float_as_uint(stage_g) & 0x80000000u;
+        if (ind) {
+            const int inst = wave % NI;
+            int64_t y = (t + PF) * BY + inst * 64 + lane;
+            if (y >= n_y) y = n_y - 1;
+            __builtin_amdgcn_global_load_lds((global_cptr)(ind + y), (lds_ptr)(dst + OFF_I + inst * 128), 4, 0, 0);
         }
     };
 
     // per-lane pieces of the swizzled LDS addresses (elements)
-    int a_off[4];  // operand reads of the score product: chunk kk*2 + hi of row lo
-#pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) a_off[k4] = lo * D + (((k4 * 2 + hi) ^ swz(lo)) * 8);
+    // Every swizzled offset is one of two per-lane bases XORed with a compile-time constant: the chunk index of an
+    // operand read is (kk*2) ^ hi ^ swz(row), that of a transpose read (mb*4) ^ (cb*2 + tb/2) ^ swz(row), and the
+    // row part of the offset has no bits in common with the chunk part.  Where registers are short (LEAN) the XOR is
+    // redone at every read instead of being kept in a register per constant.
+    constexpr bool LEAN = (D >= 256) || (D >= 128 && MODE != MODE_FWD);
+    const int a_base = lo * D + ((hi ^ swz<CPR>(lo)) * 8);  // operand reads of the score product: row lo, chunk kk*2 + hi
     const int j16 = lane & 15, ta = j16 >> 2, tb = j16 & 3, cb = (lane >> 4) & 1;
-    int t_off[2];  // transpose reads of the second product: row hi*4 + ta, chunk mb*4 + cb*2 + tb/2
-#pragma unroll
-    for (int m2 = 0; m2 < 2; ++m2)
-        t_off[m2] = (hi * 4 + ta) * D + (((m2 * 4 + cb * 2 + (tb >> 1)) ^ swz(hi * 4 + ta)) * 8) + (tb & 1) * 4;
+    // transpose reads of the second product: rows hi*4 + ta and 8 below (whose swizzle differs in bit 1), chunk
+    // mb*4 + cb*2 + tb/2, four elements per lane
+    const int t_row = hi * 4 + ta;
+    const int t_base0 = t_row * D + (((cb * 2 + (tb >> 1)) ^ swz<CPR>(t_row)) * 8) + (tb & 1) * 4;
+    const int t_base1 = (t_base0 ^ 16) + 8 * D;
+    auto xor_bits = [&](int base, int bits) -> int {
+        if (LEAN) {  // opaque to the optimiser, so it stays inside the loop
+            int r;
+            asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "s"(bits), "v"(base));
+            return r;
+        }
+        return base ^ bits;
+    };
 
-    // A tile is NSB sub-tiles of 32 streamed rows.  The sub-tile loop is unrolled and software-pipelined inside the
-    // wavefront: the matrix instructions of the next score tile are issued before the exponentials of the current one,
-    // so the matrix pipe (asynchronous) works on them, and on the second product of the previous sub-tile, while the
-    // vector unit does the softmax arithmetic.  Matrix and vector work per sub-tile are about equal at d = 64
-    // (measured 122 ns against 120 ns per SIMD), and two or three wavefronts per SIMD do not overlap them on their own.
-    // The short last tile of the streamed range takes a separate copy of the code (RAGGED), so that full tiles have
-    // no branch or select in this loop.
     constexpr int NSB = BY / 32;
-    auto scores = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG]) {
+    constexpr bool BWD = (MODE != MODE_FWD);
+    typedef uint32_t gp_t[XG][8];  // probabilities / coefficients of one sub-tile as bf16 pairs: B operand of the second product
+
+    // ---- the four pieces of a sub-tile: operand reads, score product, softmax arithmetic, second product
+    auto load_ops = [&](const uint16_t *tile, int sb, uint4 (&op)[KK]) {
+        const uint16_t *arow = tile + sb * 32 * D;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            op[kk] = *reinterpret_cast<const uint4 *>(arow + xor_bits(a_base, ((kk * 2) & SM) * 8) + (kk / NA) * (NA * 16));
+    };
+    auto mfma_scores = [&](const uint4 (&op)[KK], f32x16 (&sv)[XG]) {
 #pragma unroll
         for (int g = 0; g < XG; ++g)
 #pragma unroll
             for (int q = 0; q < 16; ++q) sv[g][q] = 0.f;
-        const uint16_t *arow = tile + sb * 32 * D;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const uint4 av = *reinterpret_cast<const uint4 *>(arow + a_off[kk & 3] + (kk >> 2) * 64);
+        for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
             for (int g = 0; g < XG; ++g)
-                sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(av), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
-        }
+                sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[kk]), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
     };
-    // softmax arithmetic of one sub-tile, and (backward) its second product
-    auto consume = [&](const uint16_t *tile, const float *yc, const uint32_t *ys, int sb, f32x16 (&sv)[XG], int rows_here,
-                       auto ragged_tag) {
+    // accumulator register q of lane (lo, hi) holds streamed row y = sb*32 + (q/4)*8 + hi*4 + q%4
+    auto softmax = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG], gp_t &gp, int rows_here, auto ragged_tag) {
         constexpr bool RAGGED = decltype(ragged_tag)::value;
-        // accumulator register q of lane (lo, hi) holds y = sb*32 + (q/4)*8 + hi*4 + q%4
         const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
         if (MODE == MODE_FWD) {
 #pragma unroll
@@ -379,27 +469,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                 for (int q = 3; q < 15; q += 2) tm = max3(tm, sv[g][q], sv[g][q + 1]);
                 const float mn = max3(run_m[g], tm * kLog2e, sv[g][15] * kLog2e);
                 if (!RAGGED || mn > -INFINITY) {  // a full sub-tile always has a finite maximum
-                    float part = 0.f;
+                    float part[4] = {0.f, 0.f, 0.f, 0.f};  // four short chains instead of one long one
 #pragma unroll
-                    for (int q = 0; q < 16; ++q) part += __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, -mn));
-                    run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + part;
+                    for (int q = 0; q < 16; ++q) part[q & 3] += __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, -mn));
+                    run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + ((part[0] + part[1]) + (part[2] + part[3]));
                     run_m[g] = mn;
                 }
             }
         } else {
-            // ---- probabilities (DH) or coefficients (DE), rounded to bf16, as the B operand of the second product
-            uint32_t gp[XG][8];
+            const float *yc = reinterpret_cast<const float *>(tile + OFF_C);
+            const uint32_t *ys = reinterpret_cast<const uint32_t *>(tile + OFF_C) + BY;
 #pragma unroll
             for (int g = 0; g < XG; ++g) {
                 float v[16];
                 if (MODE == MODE_DH) {
 #pragma unroll
                     for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, cx[g]));
-                    if (RAGGED) {
-#pragma unroll
-                        for (int q = 0; q < 16; ++q)
-                            if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
-                    }
                 } else {
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq) {
@@ -411,51 +496,129 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                         v[qq * 4 + 3] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 3], kLog2e, cy.w))) | sg.w);
                     }
                 }
+                if (RAGGED) {
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
+                }
 #pragma unroll
                 for (int q = 0; q < 16; q += 2) gp[g][q / 2] = pack2(v[q], v[q + 1]);
             }
-            // ---- out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
+        }
+    };
+    // out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
+    auto load_tr = [&](const uint16_t *tile, int sb, s16x8 (&tr)[2][MB]) {
 #pragma unroll
-            for (int k2 = 0; k2 < 2; ++k2) {
-                const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const uint16_t *tp = tbase + t_off[mb & 1] + (mb >> 1) * 64;
-                    const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)tp);
-                    const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tp + 8 * D));
-                    const s16x8 r = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    bf16x8 av;
-                    __builtin_memcpy(&av, &r, 16);
-#pragma unroll
-                    for (int g = 0; g < XG; ++g) {
-                        const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
-                        acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
-                    }
-                }
+            for (int mb = 0; mb < MB; ++mb) {
+                const int col = (mb / NT) * (NT * 32);
+                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base0, ((mb * 4) & SM) * 8) + col));
+                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base1, ((mb * 4) & SM) * 8) + col));
+                tr[k2][mb] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
-    auto process_tile = [&](int64_t t, const uint16_t *tile, const float *yc, const uint32_t *ys, auto ragged_tag) {
+    auto second = [&](const s16x8 (&tr)[2][MB], const gp_t &gp) {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                bf16x8 av;
+                __builtin_memcpy(&av, &tr[k2][mb], 16);
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
+                    acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
+                }
+            }
+    };
+
+    // A tile is NSB sub-tiles of 32 streamed rows.  Matrix and vector work per sub-tile are about equal at d = 64
+    // (measured 122 ns against 120 ns per SIMD); the matrix pipe is asynchronous, but a wavefront issues in order,
+    // and neither two nor three wavefronts per SIMD overlap the two units on their own.  So the sub-tile loop is
+    // unrolled and software-pipelined inside the wavefront: while the softmax arithmetic of sub-tile k runs, the
+    // matrix pipe works through the second product of sub-tile k - 1 and the score product of sub-tile k + 1, one
+    // matrix instruction per slice of vector work, and the LDS operands of a product are requested a phase ahead of
+    // it.  The compiler's scheduler is told that order explicitly; left alone it issues the matrix instructions of a
+    // whole tile first and the vector work after them.
+    // The short last tile of the streamed range takes a separate copy of the code (RAGGED), so that full tiles have
+    // no branch or select in this loop.
+    constexpr int NM_S = KK * XG;                 // matrix instructions of a score product
+    constexpr int NM_P = BWD ? 2 * MB * XG : 0;   // ... of a second product
+    constexpr int N_TR = 4 * MB;                  // transpose reads of a second product
+    constexpr int VALU_C = XG * (MODE == MODE_FWD ? 56 : (MODE == MODE_DH ? 42 : 58));  // vector instructions of a softmax
+    auto process_tile = [&](int64_t t, const uint16_t *tile, auto ragged_tag) {
         // rows of this tile that exist; only the last tile of the streamed range can be short
         const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
         if (SWP) {
-            f32x16 sa[XG], sb_[XG];
-            scores(tile, 0, sa);
+            static_assert(!SWP || NSB % 2 == 0, "the pipelined loop alternates between two register sets");
+            uint4 op[2][KK];
+            f32x16 sv[2][XG];
+            gp_t gp[2];
+            s16x8 tr[2][MB];
+            // Forward: operands two sub-tiles ahead (nothing else covers their latency).  Backward: one ahead, and the
+            // second product of the previous sub-tile goes to the matrix pipe before the score product that needs them.
+            constexpr int OPD = BWD ? 1 : 2;
+            load_ops(tile, 0, op[0]);
+            if (OPD == 2 && NSB > 1) load_ops(tile, 1, op[1]);
+            mfma_scores(op[0], sv[0]);
+            __builtin_amdgcn_sched_group_barrier(0x100, OPD * KK, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, NM_S, 0);
 #pragma unroll
-            for (int sb = 0; sb < NSB; sb += 2) {
-                if (sb + 1 < NSB) scores(tile, sb + 1, sb_);
-                consume(tile, yc, ys, sb, sa, rows_here, ragged_tag);
-                if (sb + 1 < NSB) {
-                    if (sb + 2 < NSB) scores(tile, sb + 2, sa);
-                    consume(tile, yc, ys, sb + 1, sb_, rows_here, ragged_tag);
+            for (int k = 0; k < NSB; ++k) {
+                const int c = k & 1, n = c ^ 1;
+                const int opn = (OPD == 2) ? n : 0, opl = (OPD == 2) ? c : 0;  // set S(k+1) reads / set loaded now
+                if (k + OPD < NSB) load_ops(tile, k + OPD, op[opl]);
+                if (BWD && k > 0) second(tr, gp[n]);
+                if (k + 1 < NSB) mfma_scores(op[opn], sv[n]);
+                softmax(tile, k, sv[c], gp[c], rows_here, ragged_tag);
+                if (BWD) load_tr(tile, k, tr);
+                // ---- issue order of this phase
+                const int n_mfma = ((BWD && k > 0) ? NM_P : 0) + (k + 1 < NSB ? NM_S : 0);
+                if (k + OPD < NSB) __builtin_amdgcn_sched_group_barrier(0x100, KK, 0);
+                if (n_mfma == NM_P + NM_S) {
+#pragma unroll
+                    for (int i = 0; i < NM_P + NM_S; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (VALU_C + NM_P + NM_S - 1) / (NM_P + NM_S), 0);
+                    }
+                } else if (n_mfma == NM_S) {
+#pragma unroll
+                    for (int i = 0; i < NM_S; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (VALU_C + NM_S - 1) / NM_S, 0);
+                    }
+                } else if (n_mfma > 0) {
+#pragma unroll
+                    for (int i = 0; i < NM_P; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, (VALU_C + (NM_P > 0 ? NM_P : 1) - 1) / (NM_P > 0 ? NM_P : 1), 0);
+                    }
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x002, VALU_C, 0);
                 }
+                if (BWD) __builtin_amdgcn_sched_group_barrier(0x100, N_TR, 0);
+            }
+            if (BWD) {
+                second(tr, gp[(NSB - 1) & 1]);
+                __builtin_amdgcn_sched_group_barrier(0x008, NM_P, 0);
             }
         } else {
 #pragma unroll 1
             for (int sb = 0; sb < NSB; ++sb) {
+                uint4 op[KK];
                 f32x16 sv[XG];
-                scores(tile, sb, sv);
-                consume(tile, yc, ys, sb, sv, rows_here, ragged_tag);
+                gp_t gp;
+                load_ops(tile, sb, op);
+                mfma_scores(op, sv);
+                softmax(tile, sb, sv, gp, rows_here, ragged_tag);
+                if (BWD) {
+                    s16x8 tr[2][MB];
+                    load_tr(tile, sb, tr);
+                    second(tr, gp);
+                }
             }
         }
     };
@@ -464,40 +627,76 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     const bool tail_ragged = (n_y % BY) != 0 && t_end == n_tiles && t_end > t_begin;
     const int64_t t_stop = tail_ragged ? t_end - 1 : t_end;  // tiles [t_begin, t_stop) are full
 
+    // Step t: start the group of tile t + PF (into the buffer that tile t - 1 has just left), work on tile t, then
+    // wait until tile t + 1 has landed: the groups issued after it are those of tiles t + 2 .. t + PF.
+    auto wait_for_next = [&](int64_t t) {
+        int younger = 0;
+#pragma unroll
+        for (int k = 2; k <= PF; ++k) younger += (t + k < t_end) ? 1 : 0;
+        wait_all_but<LPW>(younger, group_extras);
+    };
+    // Keeps the arithmetic of a tile in front of the wait that follows it: without a use at this point the compiler
+    // sinks the whole softmax update below the wait, into the next step, where no matrix work is left to overlap it.
+    auto pin_results = [&]() {
+        if (MODE == MODE_FWD) {
+#pragma unroll
+            for (int g = 0; g < XG; ++g) asm volatile("" : "+v"(run_m[g]), "+v"(run_s[g]));
+        }
+    };
+    auto step = [&](int64_t t, const uint16_t *cur, uint16_t *nxt) {
+        if (t + PF < t_end) {
+            int32_t rows[LPW];
+            rows_from_lds(t + PF, cur, rows);
+            issue_group(t + PF, rows, nxt);
+        }
+        process_tile(t, cur, Full{});
+        pin_results();
+        wait_for_next(t);
+        barrier_keep_loads();
+    };
     if (t_begin < t_end) {
-        fetch_rows(t_begin);
-        issue_tile(t_begin, tileA);
-        publish_consts(ycA, ysA);
+        int32_t rows[PF][LPW];
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (t_begin + j < t_end) rows_from_global(t_begin + j, rows[j]);
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (t_begin + j < t_end) issue_group(t_begin + j, rows[j], buf_at(j));
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (DUAL) {
-        for (int64_t t = t_begin; t < t_stop; t += 2) {
-            if (t + 1 < t_end) issue_tile(t + 1, tileB);
-            process_tile(t, tileA, ycA, ysA, Full{});
-            if (t + 1 < t_end) publish_consts(ycB, ysB);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+    wait_for_next(t_begin - 1);
+    barrier_keep_loads();
+    if (NBUF == 4) {
+        for (int64_t t = t_begin; t < t_stop; t += 4) {
+            step(t, buf0, buf3);
             if (t + 1 >= t_stop) break;
-            if (t + 2 < t_end) issue_tile(t + 2, tileA);
-            process_tile(t + 1, tileB, ycB, ysB, Full{});
-            if (t + 2 < t_end) publish_consts(ycA, ysA);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+            step(t + 1, buf1, buf0);
+            if (t + 2 >= t_stop) break;
+            step(t + 2, buf2, buf1);
+            if (t + 3 >= t_stop) break;
+            step(t + 3, buf3, buf2);
+        }
+    } else if (NBUF == 3) {
+        for (int64_t t = t_begin; t < t_stop; t += 3) {
+            step(t, buf0, buf2);
+            if (t + 1 >= t_stop) break;
+            step(t + 1, buf1, buf0);
+            if (t + 2 >= t_stop) break;
+            step(t + 2, buf2, buf1);
+        }
+    } else if (NBUF == 2) {
+        for (int64_t t = t_begin; t < t_stop; t += 2) {
+            step(t, buf0, buf1);
+            if (t + 1 >= t_stop) break;
+            step(t + 1, buf1, buf0);
         }
     } else {
         for (int64_t t = t_begin; t < t_stop; ++t) {
-            const bool odd = ((t - t_begin) & 1) != 0;
-            if (t + 1 < t_end) issue_tile(t + 1, odd ? tileA : tileB);
-            process_tile(t, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA, Full{});
-            if (t + 1 < t_end) publish_consts(odd ? ycA : ycB, odd ? ysA : ysB);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+            const int s = (int)((t - t_begin) & 1);
+            step(t, buf_at(s), buf_at(s ^ 1));
         }
     }
-    if (tail_ragged) {  // its rows were fetched by the step before (or by the prologue) and the barrier has passed
-        const bool odd = ((t_stop - t_begin) & 1) != 0;
-        process_tile(t_stop, odd ? tileB : tileA, odd ? ycB : ycA, odd ? ysB : ysA, Ragged{});
+    if (tail_ragged) {  // its group was issued with the others, and the last wait above was for all loads
+        process_tile(t_stop, buf_at((int)((t_stop - t_begin) % NB)), Ragged{});
         __syncthreads();  // the dE epilogue reuses the tile buffers
     }
 
@@ -586,7 +785,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         // dE_neg^T sits in the accumulators with the hidden index in registers and the candidate row on the lanes.
         // Turn each 32x32 block round through LDS (the streamed tiles are dead by now) so that one atomic
         // instruction adds 32 consecutive floats to each of two table rows.
-        float *tbuf = reinterpret_cast<float *>((wave & 1) ? tileB : tileA) + (wave >> 1) * (32 * 33);  // 2 per buffer
+        float *tbuf = reinterpret_cast<float *>(buf_at(wave & 1)) + (wave >> 1) * (32 * 33);  // 2 per buffer
+        int64_t *xrow_s = reinterpret_cast<int64_t *>(reinterpret_cast<float *>(buf0) + (NW / 2) * (32 * 33));
 #pragma unroll
         for (int g = 0; g < XG; ++g) xrow_s[(wave * XG + g) * 32 + lo] = x_ok[g] ? xrow[g] : -1;  // both half-waves agree
         __syncthreads();
@@ -885,13 +1085,13 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots)
     return best;
 }
 
-template <int D, int MODE, int BY, int NW, int XG, int MINB, bool DUAL>
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF>
 hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
 {
     constexpr int XPB = NW * XG * 32;
     const int64_t xblocks = (n_x + XPB - 1) / XPB;
     if (xblocks == 0) return hipSuccess;
-    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>, NW * 64);
+    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF>, NW * 64);
     if (MODE == MODE_DE) {
         // every split of the position range pays n_cols * d atomics: keep them below about a quarter of the matrix
         // time of the pass (4 n_cols d N flop at ~1 PFLOP/s against ~300 G atomics/s) => splits <= 3e-4 N
@@ -905,20 +1105,26 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
         blocks += a.pos_blocks;
     }
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
-    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, DUAL>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
+    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
 {
-    constexpr int BY = 8192 / D;               // 16 KiB of bf16 per tile buffer: 128 rows at d = 64, 32 rows at d = 256
-    constexpr int MINB_F = (D <= 64) ? 3 : 2;  // forward: register budget 168 at d = 64, else 256
+    // Forward: 16 KiB of bf16 per tile buffer (128 rows at d = 64, 32 rows at d = 256); three blocks per compute unit
+    // at d = 64 (register budget 168), else two.
+    constexpr int BY = 8192 / D;
+    constexpr int MINB_F = (D <= 64) ? 3 : 2;
+    constexpr int BY_B = BY;
     constexpr int MINB = 2;                    // backward: 256 registers per wavefront
-    constexpr bool DUAL = (D <= 128);
-    // LDS delivers about 64 bytes per clock per compute unit, half of what four SIMDs need to keep the matrix cores
-    // busy when every matrix instruction fetches a fresh operand.  Two groups of stationary rows per wavefront use
-    // each LDS operand twice; the backward accumulators leave room for that up to d = 64.
+    // LDS buffers in flight, 18 KiB each: three blocks per compute unit leave room for three, two blocks for four.
+    // At d = 256 the unrolled loop does not fit the register file (accumulators d/2 and stationary rows d/4 of the
+    // 256 registers) and the rolled two-buffer form is used.
+    constexpr int NBUF_F = (D <= 64) ? 3 : (D <= 128 ? 4 : 0);
+    constexpr int NBUF_B = (D <= 128) ? 4 : 0;
+    // Two groups of stationary rows per wavefront use each LDS operand for two matrix instructions; the backward
+    // accumulators leave room for that up to d = 64.
     constexpr int XG_F = 2;
     constexpr int XG_B = (D <= 64) ? 2 : 1;
     hipError_t e = hipSuccess;
@@ -931,9 +1137,9 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     switch (pass) {
     case TILE_PASS_FWD:
         if (wide(a.N, true))
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_F, MINB_F, DUAL>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_F, 2, (D <= 128 ? 4 : 0)>(a, a.N, stream);
         else
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB_F, DUAL>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB_F, NBUF_F>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             ProfScope prof(PROF_FWD_MERGE, stream);
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
@@ -942,9 +1148,9 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         return e;
     case TILE_PASS_DH:
         if (XG_B == 2 && wide(a.N, true))
-            e = launch_tile_kernel<D, MODE_DH, BY, 4, XG_B, MINB, DUAL>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_DH, BY_B, 4, XG_B, MINB, NBUF_B>(a, a.N, stream);
         else
-            e = launch_tile_kernel<D, MODE_DH, BY, 4, 1, MINB, DUAL>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_DH, BY_B, 4, 1, MINB, NBUF_B>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             ProfScope prof(PROF_DH_MERGE, stream);
@@ -954,8 +1160,8 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         return e;
     case TILE_PASS_DE:
         if (XG_B == 2 && wide(a.n_cols, false))
-            return launch_tile_kernel<D, MODE_DE, BY, 4, XG_B, MINB, DUAL>(a, a.n_cols, stream);
-        return launch_tile_kernel<D, MODE_DE, BY, 4, 1, MINB, DUAL>(a, a.n_cols, stream);
+            return launch_tile_kernel<D, MODE_DE, BY_B, 4, XG_B, MINB, NBUF_B>(a, a.n_cols, stream);
+        return launch_tile_kernel<D, MODE_DE, BY_B, 4, 1, MINB, NBUF_B>(a, a.n_cols, stream);
     default:
         return hipErrorInvalidValue;
     }
