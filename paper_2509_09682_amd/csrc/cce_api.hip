@@ -27,7 +27,8 @@ bool use_tile(const cce_desc *d) { return d->algo != CCE_ALGO_GATHER && tile_eli
 // the launches agree.
 struct Layout {
     size_t idx, cnt, coef, de_const, part_m, part_s, part_dH, total;
-    int splits_x;   // forward / dH passes: candidate range split over this many blocks per position block
+    int splits_x;   // dH pass: candidate range split over at most this many blocks per position block
+    int splits_fwd; // forward pass: the same, with its own (cheaper) bound
     int splits_de;  // dE pass: position range split
 };
 
@@ -47,6 +48,13 @@ Layout make_layout(const cce_desc *d)
     if (sx > col_tiles / 2) sx = (int)(col_tiles / 2);
     if (sx < 1) sx = 1;
     L.splits_x = sx;
+    // The forward partials are two floats per position and split, so the forward pass may always split: with many
+    // blocks it does so only to even out the last round (the launcher decides).
+    int sf = (int)(col_tiles / 4);
+    if (sf > 8) sf = 8;
+    if (sf < sx) sf = sx;
+    if (sf < 1) sf = 1;
+    L.splits_fwd = sf;
     const int64_t cblocks = (n_cols + 127) / 128;
     int sd = (cblocks > 0) ? (int)(2048 / cblocks) : 1;
     const int64_t pos_tiles = (N + by - 1) / by;
@@ -60,8 +68,8 @@ Layout make_layout(const cce_desc *d)
     L.cnt = off;      off += align256((size_t)N * 4);
     L.coef = off;     off += align256((size_t)N * 4);
     L.de_const = off; off += align256((size_t)N * 8);
-    L.part_m = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
-    L.part_s = off;   off += (sx > 1) ? align256((size_t)sx * N * 4) : 0;
+    L.part_m = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
+    L.part_s = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
     L.part_dH = off;  off += (sx > 1) ? align256((size_t)sx * N * d->d * 4) : 0;
     L.total = off;
     return L;
@@ -290,6 +298,7 @@ cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, c
         cce::TileArgs a = cce::make_tile_args(desc, L, H, E, tgt, neg, mask, workspace);
         a.loss = loss;
         a.lse = lse;
+        a.splits = L.splits_fwd;
         return cce::launch_tile(cce::TILE_PASS_FWD, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
     }
     cce::Params p = cce::make_params(desc, H, E, tgt, neg, mask, workspace);

@@ -120,7 +120,8 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t base = chunk * kPosChunk;
     if (base >= n_pos) return;
-    {
+    const bool sorter = tid < kPosChunk;  // blocks of more than 256 threads: the rest only keep the barriers company
+    if (sorter) {
         uint64_t key = ~0ull;  // padding sorts last
         if (base + tid < n_pos) {
             const int64_t row = pos_row(a, base + tid);
@@ -135,7 +136,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
     for (int k = 2; k <= kPosChunk; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             const int partner = tid ^ j;
-            if (partner > tid) {
+            if (sorter && partner > tid) {
                 const uint64_t ka = keys[tid], kb = keys[partner];
                 const bool up = ((tid & k) == 0);
                 if ((ka > kb) == up) {
@@ -147,6 +148,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
         }
     }
 
+    if (!sorter) return;  // no barrier below this point
     float accv[CPL];
 #pragma unroll
     for (int t = 0; t < CPL; ++t) accv[t] = 0.f;
@@ -237,17 +239,22 @@ __device__ __forceinline__ void wait_all_but(int groups, int extras)
 // wavefront (XG = 2 reads every streamed operand from LDS once for two matrix instructions).  MINB: blocks per
 // compute unit the register budget is sized for.  NBUF: LDS tile buffers in the ring (2..4: separate arrays, main loop
 // unrolled NBUF times, NBUF - 1 tiles in flight; 0: two buffers in one array and a single copy of the loop body).
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF>
+// DS: wavefronts that share a group of stationary rows in the backward passes; each of them forms the full score tile
+// and keeps 1/DS of the output columns, which divides the accumulator registers by DS at the price of DS score products.
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS>
 __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 {
-    constexpr bool SWP = (BY % 64 == 0);   // the pipelined sub-tile loop alternates between two register sets
+    constexpr bool BWD_MODE = (MODE != MODE_FWD);
+    constexpr bool SWP = (BY % 64 == 0) && (D <= 128);  // the pipelined sub-tile loop alternates between two register sets
     constexpr int KK = D / 16;             // k-steps of the score product
     constexpr int MB = D / 32;             // 32-row output blocks of the second product
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SM = (CPR == 8) ? 7 : 15;  // chunk-index bits that the LDS swizzle permutes
     constexpr int NA = (KK < (SM + 1) / 2) ? KK : (SM + 1) / 2;  // distinct swizzled offsets of the operand reads
     constexpr int NT = (MB < (SM + 1) / 4) ? MB : (SM + 1) / 4;  // ... and of the transpose reads
-    constexpr int XPB = NW * XG * 32;      // stationary rows per block
+    constexpr int XPB = (NW / DS) * XG * 32;  // stationary rows per block
+    constexpr int MBH = MB / DS;           // output blocks of the second product that this wavefront accumulates
+    static_assert(DS == 1 || (MODE != MODE_FWD && DS == 2 && NW % 2 == 0 && MBH % 4 == 0), "column split: backward passes, two ways, whole swizzle periods");
     constexpr int TILE = BY * D;           // elements per LDS tile
     constexpr int LOADS = BY * CPR / 64;   // 1-KiB direct-to-LDS load instructions per tile
     static_assert(LOADS % NW == 0, "tile loads must split evenly over the wavefronts");
@@ -265,7 +272,11 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     constexpr int CI = (2 * BY / 64 < 1) ? 1 : 2 * BY / 64;  // 256-byte load instructions that fetch the constants
     constexpr int NI = IDS / 64;                             // ... and the row numbers
     static_assert(CI <= NW && NI <= NW, "every wavefront issues exactly one instruction of each kind");
-    static_assert(NW % 2 == 0 && TILE * 2 >= (NW / 2) * 32 * 33 * 4 + XPB * 8, "tile buffers too small for the dE epilogue");
+    // dE epilogue: one 32 x 33 float transpose buffer per wavefront and the row numbers of the block.  They reuse the
+    // first two tile buffers where those are big enough (two wavefronts' worth per buffer), else get an array.
+    constexpr int EPI_BYTES = NW * 32 * 33 * 4 + XPB * 8;
+    constexpr bool EPI_IN_TILES = (MODE == MODE_DE) && (NW == 4) && (TILE * 2 >= 2 * 32 * 33 * 4 + XPB * 8);
+    static_assert(NW % 2 == 0, "wavefronts pair up on the tile buffers");
 
     // Separate arrays let the compiler see that operand reads of one buffer cannot touch the buffers that loads are
     // in flight into, so it does not wait for them; the single-array form keeps one copy of the loop body where
@@ -274,6 +285,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     __shared__ __attribute__((aligned(1024))) uint16_t buf1[NBUF >= 2 ? BUF : 8];
     __shared__ __attribute__((aligned(1024))) uint16_t buf2[NBUF >= 3 ? BUF : 8];
     __shared__ __attribute__((aligned(1024))) uint16_t buf3[NBUF >= 4 ? BUF : 8];
+    __shared__ __attribute__((aligned(16))) float epi_own[(MODE == MODE_DE && !EPI_IN_TILES) ? EPI_BYTES / 4 : 4];
     auto buf_at = [&](int i) -> uint16_t * {
         if (NBUF == 0) return buf0 + (i & 1) * BUF;
         return i == 0 ? buf0 : (i == 1 ? buf1 : (i == 2 ? buf2 : buf3));
@@ -284,9 +296,11 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     const int wave = tid >> 6;
     const int lo = lane & 31;
     const int hi = lane >> 5;
+    const int xgrp = wave / DS;   // group(s) of stationary rows of this wavefront
+    const int half = wave % DS;   // its share of the output columns
 
     if (MODE == MODE_DE && (int64_t)blockIdx.x < a.pos_blocks) {  // leading blocks: scatter of the correct items
-        static_assert(NW * 64 == kPosChunk, "the scatter role expects 256 threads");
+        static_assert(NW * 64 >= kPosChunk, "the scatter role needs 256 threads");
         pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(buf0));
         return;
     }
@@ -308,7 +322,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     float cx[XG];  // DH: -lse * log2(e) of the lane's position
 #pragma unroll
     for (int g = 0; g < XG; ++g) {
-        const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+        const int64_t x = xb * XPB + (xgrp * XG + g) * 32 + lo;
         x_ok[g] = x < n_x;
         xrow[g] = (MODE == MODE_DE) ? item_row(a, x_ok[g] ? x : 0) : pos_row(a, x_ok[g] ? x : 0);
         const uint16_t *xp = Xbase + xrow[g] * D;
@@ -319,7 +333,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
             cx[g] = -a.lse_in[xrow[g]] * kLog2e;
             // The dE pass wants g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|) for every position it
             // streams: offset and sign are filed here under the compacted index, where that pass finds them in order.
-            if (split == 0 && hi == 0 && x_ok[g]) {
+            if (split == 0 && hi == 0 && half == 0 && x_ok[g]) {
                 const float gg = a.g ? a.g[xrow[g]] : 1.f;
                 a.de_const[x] = __float_as_uint(cx[g] + __builtin_amdgcn_logf(fabsf(gg)));
                 a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
@@ -332,12 +346,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     const int64_t t_begin = n_tiles * split / a.splits;
     const int64_t t_end = n_tiles * (split + 1) / a.splits;
 
-    f32x16 acc[XG][MODE == MODE_FWD ? 1 : MB];
+    f32x16 acc[XG][MODE == MODE_FWD ? 1 : MBH];
     if (MODE != MODE_FWD) {
 #pragma unroll
         for (int g = 0; g < XG; ++g)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
                 for (int q = 0; q < 16; ++q) acc[g][mb][q] = 0.f;
     }
@@ -382,28 +396,46 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         }
     };
     // One load group: the rows of tile t, (dE) the constants of its rows, and the row numbers of tile t + PF.
-    auto issue_group = [&](int64_t t, const int32_t (&rows)[LPW], uint16_t *dst) {
+    // Byte offset inside a streamed row of the chunk that instruction i of this lane fetches: the same for every tile.
+    // A load then costs one shift-add per lane on top of the row number, as long as the streamed table is below
+    // 4 GiB (32-bit offsets from a uniform base); larger tables take 64-bit addresses.
+    uint32_t chunk_ofs[LPW];
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            const int inst = wave + i * NW;
-            const int L = inst * 64 + lane;
-            const int r = L / CPR, pc = L % CPR;
-            const int c = (pc & ~SM) | ((pc & SM) ^ swz<CPR>(r));
-            const uint16_t *src = Ybase + (int64_t)rows[i] * D + c * 8;
-            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + inst * 512), 16, 0, 0);
+    for (int i = 0; i < LPW; ++i) {
+        const int L = (wave + i * NW) * 64 + lane;
+        const int r = L / CPR, pc = L % CPR;
+        chunk_ofs[i] = (uint32_t)(((pc & ~SM) | ((pc & SM) ^ swz<CPR>(r))) * 16);
+    }
+    const bool small_table = (uint64_t)((MODE == MODE_DE) ? a.N : a.V) * (uint64_t)(D * 2) <= 0xffffffffull;
+    const char *const Ybytes = reinterpret_cast<const char *>(Ybase);
+    const uint32_t last_y = (uint32_t)(n_y - 1);
+    auto issue_group = [&](int64_t t, const int32_t (&rows)[LPW], uint16_t *dst) {
+        if (small_table) {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const uint32_t ofs = (uint32_t)rows[i] * (uint32_t)(D * 2) + chunk_ofs[i];
+                __builtin_amdgcn_global_load_lds((global_cptr)(Ybytes + ofs), (lds_ptr)(dst + (wave + i * NW) * 512), 16, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const char *src = Ybytes + (int64_t)rows[i] * (D * 2) + chunk_ofs[i];
+                __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + (wave + i * NW) * 512), 16, 0, 0);
+            }
         }
         if (MODE == MODE_DE) {  // wavefronts beyond CI repeat a load (same data, same place): group sizes stay uniform
             const int inst = wave % CI;
             const int e = inst * 64 + lane;
-            int64_t y = t * BY + (e % BY);
-            if (y >= n_y) y = n_y - 1;
+            uint32_t y = (uint32_t)(t * BY) + (uint32_t)(e % BY);  // t * BY < n_y < 2^31
+            if (y > last_y) y = last_y;
             const uint32_t *src = a.de_const + (int64_t)(e / BY) * a.N + y;
             __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + OFF_C + inst * 128), 4, 0, 0);
         }
         if (ind) {
             const int inst = wave % NI;
-            int64_t y = (t + PF) * BY + inst * 64 + lane;
-            if (y >= n_y) y = n_y - 1;
+            const int64_t t_ids = (t + PF) * BY < n_y ? (t + PF) * BY : n_y - 1;  // uniform
+            uint32_t y = (uint32_t)t_ids + (uint32_t)(inst * 64 + lane);
+            if (y > last_y) y = last_y;
             __builtin_amdgcn_global_load_lds((global_cptr)(ind + y), (lds_ptr)(dst + OFF_I + inst * 128), 4, 0, 0);
         }
     };
@@ -413,7 +445,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     // operand read is (kk*2) ^ hi ^ swz(row), that of a transpose read (mb*4) ^ (cb*2 + tb/2) ^ swz(row), and the
     // row part of the offset has no bits in common with the chunk part.  Where registers are short (LEAN) the XOR is
     // redone at every read instead of being kept in a register per constant.
-    constexpr bool LEAN = (D >= 256) || (D >= 128 && MODE != MODE_FWD);
+    constexpr bool LEAN = (D >= 256 && DS == 1 && (BWD_MODE || XG == 2)) || (D == 128 && BWD_MODE);
     const int a_base = lo * D + ((hi ^ swz<CPR>(lo)) * 8);  // operand reads of the score product: row lo, chunk kk*2 + hi
     const int j16 = lane & 15, ta = j16 >> 2, tb = j16 & 3, cb = (lane >> 4) & 1;
     // transpose reads of the second product: rows hi*4 + ta and 8 below (whose swizzle differs in bit 1), chunk
@@ -507,12 +539,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         }
     };
     // out^T[t, x] += sum_y Y[y, t] * G^T[y, x]; the A operand is read transposed from the row-major tile
-    auto load_tr = [&](const uint16_t *tile, int sb, s16x8 (&tr)[2][MB]) {
+    auto load_tr = [&](const uint16_t *tile, int sb, s16x8 (&tr)[2][MBH]) {
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
-            const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D;
+            const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D + half * (MBH * 32);  // this wavefront's columns
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; mb < MBH; ++mb) {
                 const int col = (mb / NT) * (NT * 32);
                 const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base0, ((mb * 4) & SM) * 8) + col));
                 const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base1, ((mb * 4) & SM) * 8) + col));
@@ -520,11 +552,11 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
             }
         }
     };
-    auto second = [&](const s16x8 (&tr)[2][MB], const gp_t &gp) {
+    auto second = [&](const s16x8 (&tr)[2][MBH], const gp_t &gp) {
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; mb < MBH; ++mb) {
                 bf16x8 av;
                 __builtin_memcpy(&av, &tr[k2][mb], 16);
 #pragma unroll
@@ -546,18 +578,18 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     // The short last tile of the streamed range takes a separate copy of the code (RAGGED), so that full tiles have
     // no branch or select in this loop.
     constexpr int NM_S = KK * XG;                 // matrix instructions of a score product
-    constexpr int NM_P = BWD ? 2 * MB * XG : 0;   // ... of a second product
-    constexpr int N_TR = 4 * MB;                  // transpose reads of a second product
+    constexpr int NM_P = BWD ? 2 * MBH * XG : 0;  // ... of a second product
+    constexpr int N_TR = 4 * MBH;                 // transpose reads of a second product
     constexpr int VALU_C = XG * (MODE == MODE_FWD ? 56 : (MODE == MODE_DH ? 42 : 58));  // vector instructions of a softmax
     auto process_tile = [&](int64_t t, const uint16_t *tile, auto ragged_tag) {
         // rows of this tile that exist; only the last tile of the streamed range can be short
         const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
-        if (SWP) {
+        if constexpr (SWP) {
             static_assert(!SWP || NSB % 2 == 0, "the pipelined loop alternates between two register sets");
             uint4 op[2][KK];
             f32x16 sv[2][XG];
             gp_t gp[2];
-            s16x8 tr[2][MB];
+            s16x8 tr[2][MBH];
             // Forward: operands two sub-tiles ahead (nothing else covers their latency).  Backward: one ahead, and the
             // second product of the previous sub-tile goes to the matrix pipe before the score product that needs them.
             constexpr int OPD = BWD ? 1 : 2;
@@ -606,18 +638,85 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                 __builtin_amdgcn_sched_group_barrier(0x008, NM_P, 0);
             }
         } else {
+            // Large hidden sizes: no room for a second sub-tile in flight, the other wavefront of the SIMD fills the
+            // gaps.  What must not happen is one LDS read per matrix instruction with the read issued just ahead of
+            // it, as the compiler orders them: LDS latency is several times the 32 cycles of a matrix instruction.
+            // Operands are therefore read in batches of four into two alternating register sets, and every batch is
+            // requested one batch of matrix instructions ahead of its use.
+            constexpr int BS = (DS == 1 && BWD) ? 2 : 4;  // operands per batch: two where all output columns are held
+            constexpr int NB_S = KK / BS;         // batches of the score product
+            constexpr int NB_P = 2 * MBH / BS;    // batches of the second product
+            static_assert(KK % BS == 0 && MBH % BS == 0, "whole operand batches");
 #pragma unroll 1
             for (int sb = 0; sb < NSB; ++sb) {
-                uint4 op[KK];
                 f32x16 sv[XG];
                 gp_t gp;
-                load_ops(tile, sb, op);
-                mfma_scores(op, sv);
-                softmax(tile, sb, sv, gp, rows_here, ragged_tag);
+                uint4 ob[2][BS];
+                const uint16_t *arow = tile + sb * 32 * D;
+                auto read_batch = [&](int b, uint4 (&dst)[BS]) {
+#pragma unroll
+                    for (int i = 0; i < BS; ++i) {
+                        const int kk = b * BS + i;
+                        dst[i] = *reinterpret_cast<const uint4 *>(arow + xor_bits(a_base, ((kk * 2) & SM) * 8) + (kk / NA) * (NA * 16));
+                    }
+                };
+#pragma unroll
+                for (int g = 0; g < XG; ++g)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) sv[g][q] = 0.f;
+                read_batch(0, ob[0]);
+                if (NB_S > 1) read_batch(1, ob[1]);
+#pragma unroll
+                for (int b = 0; b < NB_S; ++b) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < BS; ++i)
+#pragma unroll
+                        for (int g = 0; g < XG; ++g)
+                            sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ob[b & 1][i]), as_bf16x8(xr[g][b * BS + i]), sv[g], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (b + 2 < NB_S) read_batch(b + 2, ob[b & 1]);
+                }
                 if (BWD) {
-                    s16x8 tr[2][MB];
-                    load_tr(tile, sb, tr);
-                    second(tr, gp);
+                    // transpose reads of the first two batches go out before the softmax arithmetic and land under it
+                    s16x8 tb[2][BS];
+                    auto read_tr_batch = [&](int b, s16x8 (&dst)[BS]) {
+                        const int k2 = b / (MBH / BS);
+                        const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D + half * (MBH * 32);
+#pragma unroll
+                        for (int i = 0; i < BS; ++i) {
+                            const int mb = (b % (MBH / BS)) * BS + i;
+                            const int col = (mb / NT) * (NT * 32);
+                            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base0, ((mb * 4) & SM) * 8) + col));
+                            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base1, ((mb * 4) & SM) * 8) + col));
+                            dst[i] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+                        }
+                    };
+                    __builtin_amdgcn_sched_barrier(0);
+                    read_tr_batch(0, tb[0]);
+                    read_tr_batch(1, tb[1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    softmax(tile, sb, sv, gp, rows_here, ragged_tag);
+#pragma unroll
+                    for (int b = 0; b < NB_P; ++b) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        const int k2 = b / (MBH / BS);
+#pragma unroll
+                        for (int i = 0; i < BS; ++i) {
+                            const int mb = (b % (MBH / BS)) * BS + i;
+                            bf16x8 av;
+                            __builtin_memcpy(&av, &tb[b & 1][i], 16);
+#pragma unroll
+                            for (int g = 0; g < XG; ++g) {
+                                const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
+                                acc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, as_bf16x8(bv), acc[g][mb], 0, 0, 0);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (b + 2 < NB_P) read_tr_batch(b + 2, tb[b & 1]);
+                    }
+                } else {
+                    softmax(tile, sb, sv, gp, rows_here, ragged_tag);
                 }
             }
         }
@@ -714,7 +813,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                     rm = M;
                 }
             }
-            const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+            const int64_t x = xb * XPB + (xgrp * XG + g) * 32 + lo;
             if (a.splits > 1) {
                 if (x_ok[g] && hi == 0) {
                     a.part_m[(int64_t)split * a.N + x] = rm;
@@ -738,15 +837,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     } else if (MODE == MODE_DH) {
 #pragma unroll
         for (int g = 0; g < XG; ++g) {
-            const int64_t x = xb * XPB + (wave * XG + g) * 32 + lo;
+            const int64_t x = xb * XPB + (xgrp * XG + g) * 32 + lo;
             if (a.splits > 1) {
                 if (x_ok[g]) {
                     float *dst = a.part_dH + ((int64_t)split * a.N + x) * D;
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                    for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
                         for (int qq = 0; qq < 4; ++qq)
-                            *reinterpret_cast<float4 *>(dst + mb * 32 + qq * 8 + hi * 4) = make_float4(
+                            *reinterpret_cast<float4 *>(dst + (half * MBH + mb) * 32 + qq * 8 + hi * 4) = make_float4(
                                 acc[g][mb][qq * 4], acc[g][mb][qq * 4 + 1], acc[g][mb][qq * 4 + 2], acc[g][mb][qq * 4 + 3]);
                 }
                 continue;
@@ -760,12 +859,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                 const float pp = __builtin_amdgcn_exp2f(fmaf(op, kLog2e, cx[g]));
                 const float cpos = w * pp - 1.f;  // coefficient of the correct item before the upstream gradient
                 const float gg = a.g ? a.g[xrow[g]] : 1.f;
-                if (hi == 0) a.coef[xrow[g]] = gg * cpos;
+                if (hi == 0 && half == 0) a.coef[xrow[g]] = gg * cpos;
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
+                for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq) {
-                        const int col = mb * 32 + qq * 8 + hi * 4;
+                        const int col = (half * MBH + mb) * 32 + qq * 8 + hi * 4;
                         const uint2 ev = *reinterpret_cast<const uint2 *>(erow + col);
                         const float v0 = gg * fmaf(cpos, bf16_lo(ev.x), acc[g][mb][qq * 4 + 0]);
                         const float v1 = gg * fmaf(cpos, bf16_hi(ev.x), acc[g][mb][qq * 4 + 1]);
@@ -785,24 +884,26 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         // dE_neg^T sits in the accumulators with the hidden index in registers and the candidate row on the lanes.
         // Turn each 32x32 block round through LDS (the streamed tiles are dead by now) so that one atomic
         // instruction adds 32 consecutive floats to each of two table rows.
-        float *tbuf = reinterpret_cast<float *>(buf_at(wave & 1)) + (wave >> 1) * (32 * 33);  // 2 per buffer
-        int64_t *xrow_s = reinterpret_cast<int64_t *>(reinterpret_cast<float *>(buf0) + (NW / 2) * (32 * 33));
+        float *tbuf = EPI_IN_TILES ? reinterpret_cast<float *>(buf_at(wave & 1)) + (wave >> 1) * (32 * 33)  // 2 per buffer
+                                   : epi_own + wave * (32 * 33);
+        int64_t *xrow_s = EPI_IN_TILES ? reinterpret_cast<int64_t *>(reinterpret_cast<float *>(buf0) + 2 * (32 * 33))
+                                       : reinterpret_cast<int64_t *>(epi_own + NW * (32 * 33));
 #pragma unroll
-        for (int g = 0; g < XG; ++g) xrow_s[(wave * XG + g) * 32 + lo] = x_ok[g] ? xrow[g] : -1;  // both half-waves agree
+        for (int g = 0; g < XG; ++g) xrow_s[(xgrp * XG + g) * 32 + lo] = x_ok[g] ? xrow[g] : -1;  // both half-waves agree
         __syncthreads();
 #pragma unroll
         for (int g = 0; g < XG; ++g) {
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int mb = 0; mb < MBH; ++mb) {
 #pragma unroll
                 for (int q = 0; q < 16; ++q) tbuf[lo * 33 + (q / 4) * 8 + hi * 4 + (q % 4)] = acc[g][mb][q];
                 __syncthreads();
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int xl = r * 2 + hi;
-                    const int64_t row = xrow_s[(wave * XG + g) * 32 + xl];
+                    const int64_t row = xrow_s[(xgrp * XG + g) * 32 + xl];
                     const float v = tbuf[xl * 33 + lo];
-                    if (row >= 0) unsafeAtomicAdd(a.dE + row * D + mb * 32 + lo, v);
+                    if (row >= 0) unsafeAtomicAdd(a.dE + row * D + (half * MBH + mb) * 32 + lo, v);
                 }
                 __syncthreads();
             }
@@ -1068,9 +1169,11 @@ int resident_blocks(K kernel, int threads)
 
 // Split factor in [1, max_splits] that wastes the least of the last round of blocks; ties go to the smaller factor,
 // and a factor is only raised for a gain of at least five percent.
-inline int pick_splits(int64_t xblocks, int max_splits, int slots)
+inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_merge)
 {
-    if (xblocks * 4 > slots) return 1;  // enough blocks already: a split costs partial results and a merge
+    // enough blocks already: a split costs partial results and a merge.  Where the merge is cheap (forward: two floats
+    // per position and split) a grid of a few rounds is still split to even out its last round.
+    if (xblocks * 4 > slots && !(cheap_merge && xblocks > slots && xblocks < 8 * (int64_t)slots)) return 1;
     int best = 1;
     double best_eff = 0.0;
     for (int s = 1; s <= max_splits; ++s) {
@@ -1085,27 +1188,27 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots)
     return best;
 }
 
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF>
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1>
 hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
 {
-    constexpr int XPB = NW * XG * 32;
+    constexpr int XPB = (NW / DS) * XG * 32;
     const int64_t xblocks = (n_x + XPB - 1) / XPB;
     if (xblocks == 0) return hipSuccess;
-    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF>, NW * 64);
+    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>, NW * 64);
     if (MODE == MODE_DE) {
         // every split of the position range pays n_cols * d atomics: keep them below about a quarter of the matrix
         // time of the pass (4 n_cols d N flop at ~1 PFLOP/s against ~300 G atomics/s) => splits <= 3e-4 N
         const int cap = (int)(a.N * 5e-4) < 8 ? 8 : (int)(a.N * 5e-4);
         if (a.splits > cap) a.splits = cap;
     }
-    a.splits = pick_splits(xblocks, a.splits, slots);
+    a.splits = pick_splits(xblocks, a.splits, slots, MODE == MODE_FWD);
     int64_t blocks = xblocks * a.splits;
     if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
         a.pos_blocks = (a.N + kPosChunk - 1) / kPosChunk;
         blocks += a.pos_blocks;
     }
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
-    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
+    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -1116,13 +1219,18 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     // at d = 64 (register budget 168), else two.
     constexpr int BY = 8192 / D;
     constexpr int MINB_F = (D <= 64) ? 3 : 2;
+    // d = 256: every block streams the whole other operand from L2 (about 12 TB/s over the chip for direct-to-LDS
+    // loads), so the rows it keeps stationary decide the traffic: eight wavefronts per block, one block per compute
+    // unit.  The backward accumulators for all columns (d/2 registers) plus the stationary rows (d/4) leave little of
+    // the 256-register budget: operands are read two at a time there.
+    constexpr int NW_L = (D <= 128) ? 4 : 8;
+    constexpr int DS_B = 1;
     constexpr int BY_B = BY;
-    constexpr int MINB = 2;                    // backward: 256 registers per wavefront
-    // LDS buffers in flight, 18 KiB each: three blocks per compute unit leave room for three, two blocks for four.
-    // At d = 256 the unrolled loop does not fit the register file (accumulators d/2 and stationary rows d/4 of the
-    // 256 registers) and the rolled two-buffer form is used.
-    constexpr int NBUF_F = (D <= 64) ? 3 : (D <= 128 ? 4 : 0);
-    constexpr int NBUF_B = (D <= 128) ? 4 : 0;
+    constexpr int MINB = (D <= 128) ? 2 : 1;   // backward: 256 registers per wavefront
+    // LDS buffers in flight, 18 KiB each: three blocks per compute unit leave room for three of them, two blocks or
+    // one for four.
+    constexpr int NBUF_F = (D <= 64) ? 3 : (D <= 128 ? 4 : 2);
+    constexpr int NBUF_B = (D <= 128) ? 4 : 2;
     // Two groups of stationary rows per wavefront use each LDS operand for two matrix instructions; the backward
     // accumulators leave room for that up to d = 64.
     constexpr int XG_F = 2;
@@ -1131,26 +1239,31 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     // Two groups want 256 stationary rows per block: worth it when that still gives about two blocks per compute
     // unit, either directly or because the streamed range is being split anyway.
     auto wide = [&](int64_t n_x, bool may_split) {
-        const int64_t xb = (n_x + 255) / 256;
+        const int64_t xb = (n_x + NW_L * 64 - 1) / (NW_L * 64);
+        if (NW_L == 8) return xb >= 256;  // one block per compute unit: at least one full round of the coarser unit
         return xb >= 300 || (may_split && xb < 120 && xb * a.splits >= 480);
     };
     switch (pass) {
     case TILE_PASS_FWD:
         if (wide(a.N, true))
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, XG_F, 2, (D <= 128 ? 4 : 0)>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, XG_F, (D <= 128 ? 2 : 1), (D <= 128 ? 4 : 2)>(a, a.N, stream);
         else
-            e = launch_tile_kernel<D, MODE_FWD, BY, 4, 1, MINB_F, NBUF_F>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, 1, (D <= 128 ? MINB_F : 1), NBUF_F>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             ProfScope prof(PROF_FWD_MERGE, stream);
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
             e = hipGetLastError();
         }
         return e;
-    case TILE_PASS_DH:
-        if (XG_B == 2 && wide(a.N, true))
-            e = launch_tile_kernel<D, MODE_DH, BY_B, 4, XG_B, MINB, NBUF_B>(a, a.N, stream);
-        else
-            e = launch_tile_kernel<D, MODE_DH, BY_B, 4, 1, MINB, NBUF_B>(a, a.N, stream);
+    case TILE_PASS_DH: {
+        bool done = false;
+        if constexpr (XG_B == 2) {
+            if (wide(a.N, true)) {
+                e = launch_tile_kernel<D, MODE_DH, BY_B, 4, 2, MINB, NBUF_B>(a, a.N, stream);
+                done = true;
+            }
+        }
+        if (!done) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             ProfScope prof(PROF_DH_MERGE, stream);
@@ -1158,10 +1271,12 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
             e = hipGetLastError();
         }
         return e;
+    }
     case TILE_PASS_DE:
-        if (XG_B == 2 && wide(a.n_cols, false))
-            return launch_tile_kernel<D, MODE_DE, BY_B, 4, XG_B, MINB, NBUF_B>(a, a.n_cols, stream);
-        return launch_tile_kernel<D, MODE_DE, BY_B, 4, 1, MINB, NBUF_B>(a, a.n_cols, stream);
+        if constexpr (XG_B == 2) {
+            if (wide(a.n_cols, false)) return launch_tile_kernel<D, MODE_DE, BY_B, 4, 2, MINB, NBUF_B>(a, a.n_cols, stream);
+        }
+        return launch_tile_kernel<D, MODE_DE, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.n_cols, stream);
     default:
         return hipErrorInvalidValue;
     }
