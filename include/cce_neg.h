@@ -70,10 +70,22 @@ typedef struct {
     int32_t mask_target_collisions; /* 1: a negative equal to the position's own target is left out of LSE and gradients */
     int32_t validate_indices;       /* 1: kernels range-check ids of valid positions, skip bad ones and raise the status word */
     int32_t algo;                   /* cce_algo */
+    int32_t reuse_forward_prep;     /* backward only, 1: the caller vouches that the workspace still holds what the
+                                       forward call with this descriptor and the same tgt / neg / mask contents left
+                                       there (nothing else wrote to it since), so the compaction of padded positions
+                                       and the collision counts are not recomputed.  0: no assumption.  With 1 and a
+                                       workspace that does not hold them the results are undefined. */
 } cce_desc;
 
-/* Bytes of device workspace both calls need for this descriptor: O(N + K*d), never O(N*K).
- * Returns 0 for an invalid descriptor.  The same workspace may be reused by later calls on the same stream. */
+/* Bytes of device workspace both calls need for this descriptor.  Returns 0 for an invalid descriptor.
+ *   shared / full mode, bf16:  20 bytes per position (compaction, collision counts, coefficients), plus partial
+ *                              results of split launches: 8 bytes per position and forward split, and, for batches
+ *                              of at most 40,960 positions, 4 d bytes per position and dH split;
+ *   per-position mode:         12 bytes per (position, negative) pair for the inverted index that turns the dE
+ *                              scatter into a gather (pairs sorted by item), 4 bytes per table row, 4 per position;
+ *   otherwise:                 a 256-byte header.
+ * No score, probability or gradient-coefficient matrix is ever stored: the workspace holds indices and per-position
+ * scalars only.  The same workspace may be reused by later calls on the same stream. */
 size_t cce_neg_workspace_bytes(const cce_desc *desc);
 
 /* Clears the workspace header (index status word).  Call once after allocating a workspace, on the stream that will
@@ -101,8 +113,9 @@ cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, c
  *   lse        [N] float            from the forward call on the same inputs
  *   grad_loss  [N] float, nullable  upstream gradient of loss_i (the paper's grad LSE); NULL = 1
  *   dH  [N,d] dH_dtype (out)        fully overwritten, rows of padded positions are zero
- *   dE  [V,d] float (in/out)        ACCUMULATED INTO with floating-point atomics: the caller zeroes it or carries
- *                                   earlier gradients; rows that no valid position indexes are left untouched
+ *   dE  [V,d] float (in/out)        ACCUMULATED INTO (floating-point atomics, or one read-modify-write per row in
+ *                                   per-position mode): the caller zeroes it or carries earlier gradients; rows that
+ *                                   no valid position indexes are left untouched
  * With G_ij = grad_loss_i * (softmax_ij - [j is the correct item]):
  *   dH_i = sum_j G_ij E_{c_ij},   dE_{c_ij} += G_ij H_i.
  */
@@ -123,7 +136,7 @@ cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *h
  * makes is bracketed by a pair of HIP events on the launch stream.  cce_neg_profile_read waits for the recorded events,
  * adds the elapsed time per kernel family and returns the number of families written (at most max):
  *   names     [max][32] char (HOST)   family name, NUL-terminated: "gather_fwd", "gather_bwd", "prep", "tile_fwd",
- *                                     "fwd_merge", "tile_dh", "dh_merge", "tile_de"
+ *                                     "fwd_merge", "tile_dh", "dh_merge", "tile_de", "index", "item_de", "pos_scatter"
  *   total_ms  [max] float (HOST)      summed duration since the last read
  *   launches  [max] int32 (HOST)      launches since the last read
  * The records are cleared by the read.  Enabling creates HIP events on demand; nothing else in the library allocates.

@@ -319,11 +319,13 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     if (cce::use_tile(desc)) {
         const cce::Layout L = cce::make_layout(desc);
         cce::PrepArgs pa = cce::make_prep_args(desc, L, tgt, neg, mask, workspace);
-        pa.dH = dH;
-        if (pa.idx || pa.cnt) {
+        // The compaction and the collision counts depend on tgt, neg and mask only: a caller that vouches for the
+        // workspace still holding what the forward call left there spares their recomputation.
+        if ((pa.idx || pa.cnt) && !desc->reuse_forward_prep) {
             if (cce::launch_prep(pa, stream) != hipSuccess) return CCE_ERR_HIP;
         }
         cce::TileArgs a = cce::make_tile_args(desc, L, H, E, tgt, neg, mask, workspace);
+        a.pos_mask = mask;  // the dH launch zeroes the rows of padded positions itself
         a.lse_in = lse;
         a.g = grad_loss;
         a.dH = dH;

@@ -21,7 +21,6 @@ struct PrepArgs {
     int32_t *idx;          // out: compacted valid positions (nullptr: no compaction wanted)
     int32_t *cnt;          // out: multiplicity of the target among the negatives (nullptr: not wanted)
     float *loss, *lse;     // forward: zeroed for padded positions (nullable)
-    void *dH;              // backward: rows of padded positions zeroed (nullable)
     int64_t N, V;
     int32_t d, K, validate, dH_bf16;
 };
@@ -47,6 +46,7 @@ struct TileArgs {
     float *part_dH;              // [splits, N, d] partial dH of split runs
     int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode
     int64_t pos_blocks;          // dE launch: blocks [0, pos_blocks) scatter the correct items, the rest run the dE pass
+    int64_t pad_blocks;          // dH launch: blocks [0, pad_blocks) zero the dH rows of padded positions (set by the launcher)
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
 };
 

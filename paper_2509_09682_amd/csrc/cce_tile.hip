@@ -235,6 +235,14 @@ __device__ __forceinline__ void wait_all_but(int groups, int extras)
     }
 }
 
+// The same, ordered behind the instruction that produced `after` (an input the instruction does not read).
+__device__ __forceinline__ float max3_after(float after, float x, float y, float z)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z), "v"(after));
+    return r;
+}
+
 // D: hidden size.  BY: streamed rows per LDS tile.  NW: wavefronts per block.  XG: groups of 32 stationary rows per
 // wavefront (XG = 2 reads every streamed operand from LDS once for two matrix instructions).  MINB: blocks per
 // compute unit the register budget is sized for.  NBUF: LDS tile buffers in the ring (2..4: separate arrays, main loop
@@ -304,7 +312,29 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(buf0));
         return;
     }
-    const int64_t bid = (MODE == MODE_DE) ? (int64_t)blockIdx.x - a.pos_blocks : (int64_t)blockIdx.x;
+    if (MODE == MODE_DH && (int64_t)blockIdx.x < a.pad_blocks) {  // leading blocks: dH rows of padded positions are zero
+        const int64_t i = (int64_t)blockIdx.x * (NW * 64) + tid;
+        if (i < a.N) {
+            bool valid = (a.pos_mask == nullptr) || (a.pos_mask[i] != 0);
+            if (valid && a.validate) {  // a position with a target out of range counts as padding
+                const int32_t ti = a.tgt[i];
+                valid = ti >= 0 && (int64_t)ti < a.V;
+            }
+            if (!valid) {
+                if (a.dH_bf16) {
+                    uint4 *row = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.dH) + i * D);
+#pragma unroll 4
+                    for (int c = 0; c < D / 8; ++c) row[c] = make_uint4(0, 0, 0, 0);
+                } else {
+                    float4 *row = reinterpret_cast<float4 *>(static_cast<float *>(a.dH) + i * D);
+#pragma unroll 4
+                    for (int c = 0; c < D / 4; ++c) row[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+        return;
+    }
+    const int64_t bid = (int64_t)blockIdx.x - (MODE == MODE_DE ? a.pos_blocks : (MODE == MODE_DH ? a.pad_blocks : 0));
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t n_x = (MODE == MODE_DE) ? a.n_cols : n_pos;
     const int64_t n_y = (MODE == MODE_DE) ? n_pos : a.n_cols;
@@ -496,10 +526,14 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                     for (int q = 0; q < 16; ++q)
                         if ((q / 4) * 8 + (q % 4) >= rem) sv[g][q] = -INFINITY;
                 }
-                float tm = max3(sv[g][0], sv[g][1], sv[g][2]);
+                // The compiler pads matrix-instruction results with the wait states their first vector reader needs,
+                // but it does not look inside inline assembly: the first reader of this score tile is therefore a
+                // plain multiply, and the max3 chain is tied behind it.
+                const float last = sv[g][15] * kLog2e;
+                float tm = max3_after(last, sv[g][0], sv[g][1], sv[g][2]);
 #pragma unroll
                 for (int q = 3; q < 15; q += 2) tm = max3(tm, sv[g][q], sv[g][q + 1]);
-                const float mn = max3(run_m[g], tm * kLog2e, sv[g][15] * kLog2e);
+                const float mn = max3(run_m[g], tm * kLog2e, last);
                 if (!RAGGED || mn > -INFINITY) {  // a full sub-tile always has a finite maximum
                     float part[4] = {0.f, 0.f, 0.f, 0.f};  // four short chains instead of one long one
 #pragma unroll
@@ -998,15 +1032,6 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(PrepArgs p)
     if (i < p.N && !valid) {
         if (p.loss) p.loss[i] = 0.f;
         if (p.lse) p.lse[i] = 0.f;
-        if (p.dH) {
-            if (p.dH_bf16) {
-                uint4 *row = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(p.dH) + i * p.d);
-                for (int c = 0; c < p.d / 8; ++c) row[c] = make_uint4(0, 0, 0, 0);
-            } else {
-                float4 *row = reinterpret_cast<float4 *>(static_cast<float *>(p.dH) + i * p.d);
-                for (int c = 0; c < p.d / 4; ++c) row[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
     }
 
     // ---- multiplicity of each target among the shared negatives: the block's targets go into an LDS hash table,
@@ -1206,6 +1231,10 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
     if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
         a.pos_blocks = (a.N + kPosChunk - 1) / kPosChunk;
         blocks += a.pos_blocks;
+    }
+    if (MODE == MODE_DH) {
+        a.pad_blocks = (a.pos_mask || a.validate) ? (a.N + NW * 64 - 1) / (NW * 64) : 0;
+        blocks += a.pad_blocks;
     }
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);

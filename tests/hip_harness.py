@@ -24,13 +24,16 @@ def to_device(w):
 
 
 def run_hip(w, *, g: Optional[np.ndarray] = "workload", algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32, validate=0,
-            use_mask=True, dE_init: Optional[np.ndarray] = None, repeat_backward: int = 1):
+            use_mask=True, dE_init: Optional[np.ndarray] = None, repeat_backward: int = 1, reuse_prep: bool = False):
     """Forward + backward on cuda:0.  Returns dict(loss, lse, dH (float32), dE (float32), status)."""
     H, E, tgt, neg, mask = to_device(w)
     if not use_mask:
         mask = None
     desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
                        dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate, algo=algo)
+    desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
+                           dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate,
+                           algo=algo, reuse_forward_prep=1 if reuse_prep else 0)
     ws = P.new_workspace(desc)
     loss = torch.full((w.N,), float("nan"), device="cuda")
     lse = torch.full((w.N,), float("nan"), device="cuda")
@@ -47,7 +50,7 @@ def run_hip(w, *, g: Optional[np.ndarray] = "workload", algo=P.CCE_ALGO_AUTO, dH
         dH = torch.full((w.N, w.d), float("nan"), device="cuda")
     dE = torch.zeros((w.V, w.d), device="cuda") if dE_init is None else torch.from_numpy(dE_init).to("cuda")
     for _ in range(repeat_backward):
-        P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g_t, dH, dE, ws)
+        P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g_t, dH, dE, ws)
     status = P.cce_neg_index_status(ws)
     torch.cuda.synchronize()
     return dict(loss=loss.cpu().numpy(), lse=lse.cpu().numpy(), dH=dH.float().cpu().numpy(), dE=dE.cpu().numpy(),

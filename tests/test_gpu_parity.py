@@ -95,6 +95,37 @@ def test_tile_path_ragged_shapes_collisions_and_duplicates(d, mode):
     check_against_oracle(w, out, TOL_BF16, g=None)
 
 
+@pytest.mark.parametrize("d", [64, 256])
+def test_backward_reusing_the_forward_preparation(d):
+    """reuse_forward_prep = 1: the backward call skips the compaction / collision pass and must give the same result
+    (masked rows of dH still exactly zero, collisions still masked)."""
+    import paper_2509_09682_amd as P
+
+    w = make_workload(f"tile_reuse_prep_d{d}", 9, 83, d, 211, 190, "bf16", NEG_SHARED, 4242 + d, pad="bernoulli", pad_p=0.35,
+                      g_kind="random", e_sigma=0.1, tgt_dist="zipf")
+    assert ((w.neg[None, :] == w.tgt[:, None]).sum(1)[w.mask != 0]).max() >= 1   # collisions on valid positions
+    a = _run(w, algo=P.CCE_ALGO_TILE, reuse_prep=True)
+    check_against_oracle(w, a, TOL_BF16)
+    b = _run(w, algo=P.CCE_ALGO_TILE, reuse_prep=False)
+    assert np.array_equal(a["dH"], b["dH"]) and np.array_equal(a["loss"], b["loss"])
+    assert tensor_rel(a["dE"], b["dE"]) <= 1e-5      # atomics: same terms, order may differ
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_forward_and_dH_are_bitwise_reproducible(d):
+    """No atomics feed loss, lse or dH: two runs on the same inputs must agree bit for bit (a vector instruction that
+    read a matrix-instruction result too early once showed up here as last-bit noise)."""
+    import paper_2509_09682_amd as P
+
+    w = make_workload(f"tile_repro_d{d}", 60, 200, d, 211, 96, "bf16", NEG_SHARED, 99 + d, pad="none", g_kind="random",
+                      e_sigma=0.1, tgt_dist="zipf")
+    a = _run(w, algo=P.CCE_ALGO_TILE)
+    for _ in range(3):
+        b = _run(w, algo=P.CCE_ALGO_TILE)
+        for name in ("loss", "lse", "dH"):
+            assert np.array_equal(a[name].view(np.uint32), b[name].view(np.uint32)), name
+
+
 def test_tile_path_many_positions_splits_the_dE_pass():
     import paper_2509_09682_amd as P
 
