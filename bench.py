@@ -21,6 +21,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+EXP_PER_S = 12.5e12           # measured v_exp_f32 rate of the whole chip (profiles/microbenchmarks.md)
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 PEAK_F32_VALU_TFLOPS = 157.3
 
@@ -114,6 +115,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the config the metric is quoted on)")
     ap.add_argument("--algo", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-reps", type=int, default=5, help="steps timed with a 1 GiB cache-evicting write in front (0 = skip)")
     ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes the padding compaction of the forward call")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
@@ -169,10 +171,17 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # timed region: K steps bracketed by synchronisation; events on the launch stream split forward and backward
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    # timed region: exactly K steps bracketed by synchronisation, nothing else on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for k in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+
+    # forward / backward split of the same steps (events on the launch stream), outside the timed region
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for k in range(args.steps):
         ev[k][0].record()
         P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
@@ -180,10 +189,22 @@ def main() -> int:
         P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
         ev[k][2].record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_step = (t1 - t0) * 1e3 / args.steps
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    # cold caches: a 1 GiB write between steps evicts L2 and the Infinity Cache
+    cold_ms = None
+    if args.cold_reps > 0:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        c = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.cold_reps)]
+        for k in range(args.cold_reps):
+            scratch.fill_(float(k))
+            c[k][0].record()
+            step()
+            c[k][1].record()
+        torch.cuda.synchronize()
+        cold_ms = float(np.median([e[0].elapsed_time(e[1]) for e in c]))
+        del scratch
 
     # dE zero-fill, reported apart from the step (dE is an accumulate-into buffer owned by the caller)
     z0, z1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -236,7 +257,8 @@ def main() -> int:
             "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
             "reuse_forward_prep": not args.no_reuse_prep,
             "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
-            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
+            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
+            "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,
             "algorithmic_gflop": flops / 1e9, "algorithmic_mbytes": bytes_min / 1e6,
             "whole_step_tflops": flops / (ms_step * 1e-3) / 1e12,
             "whole_step_frac_mfma_peak": flops / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
