@@ -57,7 +57,8 @@ def kernel_work(w, family):
 
     Matrix-core kernels: 2 * n_cols * d flop per valid position and GEMM-equivalent, n_cols = K (V for the full
     catalogue).  The forward pass is one GEMM-equivalent (scores), the dH pass two (scores recomputed, dH), the dE pass
-    one (dE; its own recomputation of the scores is overhead and does not count).
+    one (dE; its own recomputation of the scores is overhead and does not count); hidden sizes up to 128 run the dH and
+    the dE pass in one launch (tile_bwd, three).
     Row-gather kernels: the candidate rows of every valid position (K+1 rows of d elements), the ids, H, and for the
     backward pass dH and every dE row written once.
     """
@@ -71,6 +72,10 @@ def kernel_work(w, family):
         return "mfma", 2 * gemm
     if family == "tile_de":
         return "mfma", gemm
+    if family == "tile_bwd":   # dH and dE pass in one launch
+        return "mfma", 3 * gemm
+    if family == "bwd_pre":    # per valid position: H row, correct item's row, five scalars in, three out
+        return "hbm", float(nv) * (2 * w.d * esz + 32)
     n_cand = w.V if w.neg_mode == 2 else w.K + 1
     rows = float(nv) * n_cand * w.d * esz
     ids = float(nv) * (w.K if w.neg_mode == 1 else 0) * 4

@@ -136,7 +136,8 @@ cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *h
  * makes is bracketed by a pair of HIP events on the launch stream.  cce_neg_profile_read waits for the recorded events,
  * adds the elapsed time per kernel family and returns the number of families written (at most max):
  *   names     [max][32] char (HOST)   family name, NUL-terminated: "gather_fwd", "gather_bwd", "prep", "tile_fwd",
- *                                     "fwd_merge", "tile_dh", "dh_merge", "tile_de", "index", "item_de", "pos_scatter"
+ *                                     "fwd_merge", "tile_dh", "dh_merge", "tile_de", "index", "item_de", "pos_scatter",
+ *                                     "bwd_pre", "tile_bwd" (dH and dE pass in one launch)
  *   total_ms  [max] float (HOST)      summed duration since the last read
  *   launches  [max] int32 (HOST)      launches since the last read
  * The records are cleared by the read.  Enabling creates HIP events on demand; nothing else in the library allocates.

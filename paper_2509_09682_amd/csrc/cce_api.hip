@@ -223,7 +223,7 @@ bool g_prof_enabled = false;
 std::vector<ProfRecord> g_prof_records;
 std::vector<hipEvent_t> g_prof_pool;
 const char *const kProfNames[PROF_FAMILIES] = {"gather_fwd", "gather_bwd", "prep",  "tile_fwd", "fwd_merge",  "tile_dh",
-                                               "dh_merge",   "tile_de",    "index", "item_de",  "pos_scatter"};
+                                               "dh_merge",   "tile_de",    "index", "item_de",  "pos_scatter", "bwd_pre", "tile_bwd"};
 hipEvent_t prof_event()
 {
     if (!g_prof_pool.empty()) {
@@ -330,9 +330,13 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
         a.g = grad_loss;
         a.dH = dH;
         a.dE = dE;
+        a.write_consts = 1;
+        cce::TileArgs a_de = a;
+        a_de.splits = L.splits_de;
+        if (cce::tile_backward_fusable(desc->d))  // both passes in one launch, behind a small per-position pass
+            return cce::launch_tile_backward(a, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
         if (cce::launch_tile(cce::TILE_PASS_DH, a, stream) != hipSuccess) return CCE_ERR_HIP;
-        a.splits = L.splits_de;
-        return cce::launch_tile(cce::TILE_PASS_DE, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+        return cce::launch_tile(cce::TILE_PASS_DE, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
     }
     cce::Params p = cce::make_params(desc, H, E, tgt, neg, mask, workspace);
     p.lse_in = lse;

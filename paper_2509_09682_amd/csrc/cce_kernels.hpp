@@ -48,9 +48,13 @@ struct TileArgs {
     int64_t pos_blocks;          // dE launch: blocks [0, pos_blocks) scatter the correct items, the rest run the dE pass
     int64_t pad_blocks;          // dH launch: blocks [0, pad_blocks) zero the dH rows of padded positions (set by the launcher)
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
+    int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
 };
 
 enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items
+// dH and dE passes in one launch (hidden sizes up to 128): a_dh.splits / a_de.splits carry the two split bounds.
+bool tile_backward_fusable(int d);
+hipError_t launch_tile_backward(const TileArgs &a_dh, const TileArgs &a_de, hipStream_t stream);
 
 // ---- inverted-index dE of per-position negatives
 struct InvertArgs {
@@ -86,7 +90,7 @@ hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 
 // Event bracket around a kernel launch while profiling is enabled (see cce_neg_profile_enable); otherwise a no-op.
 enum { PROF_GATHER_FWD = 0, PROF_GATHER_BWD, PROF_PREP, PROF_TILE_FWD, PROF_FWD_MERGE, PROF_TILE_DH, PROF_DH_MERGE,
-       PROF_TILE_DE, PROF_INDEX, PROF_ITEM_DE, PROF_POS_SCATTER, PROF_FAMILIES };
+       PROF_TILE_DE, PROF_INDEX, PROF_ITEM_DE, PROF_POS_SCATTER, PROF_BWD_PRE, PROF_TILE_BWD, PROF_FAMILIES };
 struct ProfScope {
     ProfScope(int family, hipStream_t stream);
     ~ProfScope();

@@ -110,12 +110,12 @@ typedef s16x4 __attribute__((address_space(3))) *lds_v4;
 // registers and issues one row of atomics per run.  These blocks ride in the launch of the dE pass, after its own
 // blocks, so that their latency (sort, dependent gathers) hides under the matrix work.
 constexpr int kPosChunk = 256;
-constexpr int kPosBatch = 16;  // rows in flight per wavefront
 
 template <int D>
 __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chunk, uint64_t *keys)
 {
-    constexpr int CPL = D / 64;  // columns per lane
+    constexpr int CPL = D / 64;         // columns per lane
+    constexpr int kPosBatch = 16;        // rows in flight per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t base = chunk * kPosChunk;
@@ -249,8 +249,26 @@ __device__ __forceinline__ float max3_after(float after, float x, float y, float
 // unrolled NBUF times, NBUF - 1 tiles in flight; 0: two buffers in one array and a single copy of the loop body).
 // DS: wavefronts that share a group of stationary rows in the backward passes; each of them forms the full score tile
 // and keeps 1/DS of the output columns, which divides the accumulator registers by DS at the price of DS score products.
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS>
-__global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
+// LDS needs of one tile-kernel configuration (the kernel wrappers declare the arrays, the body gets pointers).
+template <int D, int MODE, int BY, int NW, int XG, int NBUF, int DS>
+struct TileGeom {
+    static constexpr int TILE = BY * D;
+    static constexpr int IDS = (BY < 64) ? 64 : BY;
+    static constexpr int CONSTS = (MODE == MODE_DE) ? 2 * BY : 0;
+    static constexpr int BUF = ((TILE + 2 * CONSTS + 2 * IDS + 511) / 512) * 512;  // 16-bit elements per buffer
+    static constexpr int XPB = (NW / DS) * XG * 32;
+    static constexpr int EPI_BYTES = NW * 32 * 33 * 4 + XPB * 8;
+    static constexpr bool EPI_IN_TILES = (MODE == MODE_DE) && (NW == 4) && (TILE * 2 >= 2 * 32 * 33 * 4 + XPB * 8);
+    static constexpr int BUF0 = (NBUF == 0) ? 2 * BUF : BUF;
+    static constexpr int BUF1 = (NBUF >= 2) ? BUF : 8;
+    static constexpr int BUF2 = (NBUF >= 3) ? BUF : 8;
+    static constexpr int BUF3 = (NBUF >= 4) ? BUF : 8;
+    static constexpr int EPI_OWN = (MODE == MODE_DE && !EPI_IN_TILES) ? EPI_BYTES / 4 : 4;  // floats
+};
+
+template <int D, int MODE, int BY, int NW, int XG, int NBUF, int DS>
+__device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_id, uint16_t *const buf0, uint16_t *const buf1,
+                                          uint16_t *const buf2, uint16_t *const buf3, float *const epi_own)
 {
     constexpr bool BWD_MODE = (MODE != MODE_FWD);
     constexpr bool SWP = (BY % 64 == 0) && (D <= 128);  // the pipelined sub-tile loop alternates between two register sets
@@ -286,14 +304,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     constexpr bool EPI_IN_TILES = (MODE == MODE_DE) && (NW == 4) && (TILE * 2 >= 2 * 32 * 33 * 4 + XPB * 8);
     static_assert(NW % 2 == 0, "wavefronts pair up on the tile buffers");
 
-    // Separate arrays let the compiler see that operand reads of one buffer cannot touch the buffers that loads are
-    // in flight into, so it does not wait for them; the single-array form keeps one copy of the loop body where
-    // registers are short, and leans on the second block of the compute unit.
-    __shared__ __attribute__((aligned(1024))) uint16_t buf0[NBUF == 0 ? 2 * BUF : BUF];
-    __shared__ __attribute__((aligned(1024))) uint16_t buf1[NBUF >= 2 ? BUF : 8];
-    __shared__ __attribute__((aligned(1024))) uint16_t buf2[NBUF >= 3 ? BUF : 8];
-    __shared__ __attribute__((aligned(1024))) uint16_t buf3[NBUF >= 4 ? BUF : 8];
-    __shared__ __attribute__((aligned(16))) float epi_own[(MODE == MODE_DE && !EPI_IN_TILES) ? EPI_BYTES / 4 : 4];
+    // buf0..buf3 are separate LDS arrays of the calling kernel: the compiler then sees that operand reads of one buffer
+    // cannot touch the buffers that loads are in flight into, and does not wait for them; the single-array form
+    // (NBUF = 0) keeps one copy of the loop body where registers are short.
     auto buf_at = [&](int i) -> uint16_t * {
         if (NBUF == 0) return buf0 + (i & 1) * BUF;
         return i == 0 ? buf0 : (i == 1 ? buf1 : (i == 2 ? buf2 : buf3));
@@ -307,13 +320,13 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     const int xgrp = wave / DS;   // group(s) of stationary rows of this wavefront
     const int half = wave % DS;   // its share of the output columns
 
-    if (MODE == MODE_DE && (int64_t)blockIdx.x < a.pos_blocks) {  // leading blocks: scatter of the correct items
+    if (MODE == MODE_DE && block_id < a.pos_blocks) {  // leading blocks: scatter of the correct items
         static_assert(NW * 64 >= kPosChunk, "the scatter role needs 256 threads");
-        pos_scatter_block<D>(a, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(buf0));
+        pos_scatter_block<D>(a, block_id, reinterpret_cast<uint64_t *>(buf0));
         return;
     }
-    if (MODE == MODE_DH && (int64_t)blockIdx.x < a.pad_blocks) {  // leading blocks: dH rows of padded positions are zero
-        const int64_t i = (int64_t)blockIdx.x * (NW * 64) + tid;
+    if (MODE == MODE_DH && block_id < a.pad_blocks) {  // leading blocks: dH rows of padded positions are zero
+        const int64_t i = block_id * (NW * 64) + tid;
         if (i < a.N) {
             bool valid = (a.pos_mask == nullptr) || (a.pos_mask[i] != 0);
             if (valid && a.validate) {  // a position with a target out of range counts as padding
@@ -334,7 +347,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
         }
         return;
     }
-    const int64_t bid = (int64_t)blockIdx.x - (MODE == MODE_DE ? a.pos_blocks : (MODE == MODE_DH ? a.pad_blocks : 0));
+    const int64_t bid = block_id - (MODE == MODE_DE ? a.pos_blocks : (MODE == MODE_DH ? a.pad_blocks : 0));
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t n_x = (MODE == MODE_DE) ? a.n_cols : n_pos;
     const int64_t n_y = (MODE == MODE_DE) ? n_pos : a.n_cols;
@@ -363,7 +376,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
             cx[g] = -a.lse_in[xrow[g]] * kLog2e;
             // The dE pass wants g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|) for every position it
             // streams: offset and sign are filed here under the compacted index, where that pass finds them in order.
-            if (split == 0 && hi == 0 && half == 0 && x_ok[g]) {
+            if (a.write_consts && split == 0 && hi == 0 && half == 0 && x_ok[g]) {
                 const float gg = a.g ? a.g[xrow[g]] : 1.f;
                 a.de_const[x] = __float_as_uint(cx[g] + __builtin_amdgcn_logf(fabsf(gg)));
                 a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
@@ -893,7 +906,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                 const float pp = __builtin_amdgcn_exp2f(fmaf(op, kLog2e, cx[g]));
                 const float cpos = w * pp - 1.f;  // coefficient of the correct item before the upstream gradient
                 const float gg = a.g ? a.g[xrow[g]] : 1.f;
-                if (hi == 0 && half == 0) a.coef[xrow[g]] = gg * cpos;
+                if (a.write_consts && hi == 0 && half == 0) a.coef[xrow[g]] = gg * cpos;
 #pragma unroll
                 for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
@@ -942,6 +955,77 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
                 __syncthreads();
             }
         }
+    }
+}
+
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS>
+__global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
+{
+    typedef TileGeom<D, MODE, BY, NW, XG, NBUF, DS> G;
+    __shared__ __attribute__((aligned(1024))) uint16_t buf0[G::BUF0];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf1[G::BUF1];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf2[G::BUF2];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf3[G::BUF3];
+    __shared__ __attribute__((aligned(16))) float epi_own[G::EPI_OWN];
+    tile_body<D, MODE, BY, NW, XG, NBUF, DS>(a, (int64_t)blockIdx.x, buf0, buf1, buf2, buf3, epi_own);
+}
+
+// The dH and the dE pass of one backward call in a single launch: with few positions neither pass fills the chip on
+// its own (c2: 320 + 256 blocks of one wavefront per SIMD each), and both are bound by latencies rather than by any
+// unit, so they overlap almost completely.  The dE blocks (correct-item scatter first) lead the grid, being the longer
+// ones.  Both roles share the LDS arrays; neither reads what the other writes (coef and de_const come from
+// bwd_pre_kernel).
+template <int D, int BY, int XG_DH, int XG_DE, int NBUF>
+__global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArgs a_de, int64_t de_blocks)
+{
+    typedef TileGeom<D, MODE_DH, BY, 4, XG_DH, NBUF, 1> GH;
+    typedef TileGeom<D, MODE_DE, BY, 4, XG_DE, NBUF, 1> GE;
+    constexpr int B0 = GH::BUF0 > GE::BUF0 ? GH::BUF0 : GE::BUF0, B1 = GH::BUF1 > GE::BUF1 ? GH::BUF1 : GE::BUF1;
+    constexpr int B2 = GH::BUF2 > GE::BUF2 ? GH::BUF2 : GE::BUF2, B3 = GH::BUF3 > GE::BUF3 ? GH::BUF3 : GE::BUF3;
+    __shared__ __attribute__((aligned(1024))) uint16_t buf0[B0];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf1[B1];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf2[B2];
+    __shared__ __attribute__((aligned(1024))) uint16_t buf3[B3];
+    __shared__ __attribute__((aligned(16))) float epi_own[GE::EPI_OWN];
+    // grid order: the dE role (correct-item scatter, then its tiles) ahead of the dH role (zeroing of padded rows, then
+    // its tiles); measured faster on c2 than tiles first
+    const int64_t b = (int64_t)blockIdx.x;
+    if (b < de_blocks)
+        tile_body<D, MODE_DE, BY, 4, XG_DE, NBUF, 1>(a_de, b, buf0, buf1, buf2, buf3, epi_own);
+    else
+        tile_body<D, MODE_DH, BY, 4, XG_DH, NBUF, 1>(a_dh, b - de_blocks, buf0, buf1, buf2, buf3, epi_own);
+}
+
+// Per valid position, ahead of a fused backward launch: the coefficient of the correct item g (w p+ - 1) for the
+// scatter, and offset and sign of the dE coefficients g exp(o - lse) = sign(g) 2^(o log2e - lse log2e + log2|g|) under
+// the compacted index.  D/8 lanes per position share the scalar product with the correct item's row.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_pre_kernel(TileArgs a)
+{
+    constexpr int LPR = D / 8;
+    constexpr int PPB = 256 / LPR;
+    const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
+    const int64_t x = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+    const int c = threadIdx.x % LPR;
+    const bool ok = x < n_pos;
+    const int64_t row = ok ? pos_row(a, x) : 0;
+    float op = 0.f;
+    if (ok) {
+        float h[8], e[8];
+        load8(a.H + row * D + c * 8, h);
+        load8(a.E + (int64_t)a.tgt[row] * D + c * 8, e);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) op = fmaf(h[t], e[t], op);
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) op += __shfl_xor(op, off, 64);
+    if (ok && c == 0) {
+        const float nl = -a.lse_in[row] * kLog2e;
+        const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[row] : 1.f);
+        const float gg = a.g ? a.g[row] : 1.f;
+        a.coef[row] = gg * (w * __builtin_amdgcn_exp2f(fmaf(op, kLog2e, nl)) - 1.f);
+        a.de_const[x] = __float_as_uint(nl + __builtin_amdgcn_logf(fabsf(gg)));
+        a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
     }
 }
 
@@ -1213,13 +1297,12 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_me
     return best;
 }
 
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1>
-hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
+// Split factor and leading blocks of one pass; returns the number of blocks of its grid (0: nothing to do).
+template <int MODE>
+int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots)
 {
-    constexpr int XPB = (NW / DS) * XG * 32;
-    const int64_t xblocks = (n_x + XPB - 1) / XPB;
-    if (xblocks == 0) return hipSuccess;
-    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>, NW * 64);
+    const int64_t xblocks = (n_x + xpb - 1) / xpb;
+    if (xblocks == 0) return 0;
     if (MODE == MODE_DE) {
         // every split of the position range pays n_cols * d atomics: keep them below about a quarter of the matrix
         // time of the pass (4 n_cols d N flop at ~1 PFLOP/s against ~300 G atomics/s) => splits <= 3e-4 N
@@ -1233,11 +1316,34 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
         blocks += a.pos_blocks;
     }
     if (MODE == MODE_DH) {
-        a.pad_blocks = (a.pos_mask || a.validate) ? (a.N + NW * 64 - 1) / (NW * 64) : 0;
+        a.pad_blocks = (a.pos_mask || a.validate) ? (a.N + threads - 1) / threads : 0;
         blocks += a.pad_blocks;
     }
+    return blocks;
+}
+
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1>
+hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
+{
+    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>, NW * 64);
+    const int64_t blocks = plan_tile_grid<MODE>(a, n_x, (NW / DS) * XG * 32, NW * 64, slots);
+    if (blocks == 0) return hipSuccess;
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
+    return hipGetLastError();
+}
+
+template <int D, int XG_DH, int XG_DE>
+hipError_t launch_bwd_kernel(TileArgs &a_dh, TileArgs &a_de, hipStream_t stream)
+{
+    constexpr int BY = 8192 / D, NBUF = 4;
+    static const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF>, 256);
+    const int64_t de_blocks = plan_tile_grid<MODE_DE>(a_de, a_de.n_cols, 4 * XG_DE * 32, 256, slots);
+    const int64_t dh_blocks = plan_tile_grid<MODE_DH>(a_dh, a_dh.N, 4 * XG_DH * 32, 256, slots);
+    if (de_blocks + dh_blocks == 0) return hipSuccess;
+    ProfScope prof(PROF_TILE_BWD, stream);
+    hipLaunchKernelGGL((tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF>), dim3((unsigned)(de_blocks + dh_blocks)), dim3(256), 0, stream,
+                       a_dh, a_de, de_blocks);
     return hipGetLastError();
 }
 
@@ -1311,6 +1417,41 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     }
 }
 
+template <int D>
+hipError_t launch_bwd_for_d(TileArgs a_dh, TileArgs a_de, hipStream_t stream)
+{
+    constexpr int XG_B = (D <= 64) ? 2 : 1;
+    a_dh.write_consts = 0;
+    {
+        constexpr int PPB = 256 / (D / 8);
+        ProfScope prof(PROF_BWD_PRE, stream);
+        hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)((a_dh.N + PPB - 1) / PPB)), dim3(256), 0, stream, a_dh);
+        if (hipGetLastError() != hipSuccess) return hipGetLastError();
+    }
+    // two groups of stationary rows per wavefront under the same rule as for the separate launches
+    auto wide = [&](int64_t n_x, int splits, bool may_split) {
+        const int64_t xb = (n_x + 255) / 256;
+        return XG_B == 2 && (xb >= 300 || (may_split && xb < 120 && xb * splits >= 480));
+    };
+    const bool wide_dh = wide(a_dh.N, a_dh.splits, true), wide_de = wide(a_de.n_cols, a_de.splits, false);
+    hipError_t e;
+    if constexpr (XG_B == 2) {
+        if (wide_dh && wide_de) e = launch_bwd_kernel<D, 2, 2>(a_dh, a_de, stream);
+        else if (wide_dh) e = launch_bwd_kernel<D, 2, 1>(a_dh, a_de, stream);
+        else if (wide_de) e = launch_bwd_kernel<D, 1, 2>(a_dh, a_de, stream);
+        else e = launch_bwd_kernel<D, 1, 1>(a_dh, a_de, stream);
+    } else {
+        e = launch_bwd_kernel<D, 1, 1>(a_dh, a_de, stream);
+    }
+    if (e == hipSuccess && a_dh.splits > 1) {
+        constexpr int PPB = 256 / (D / 8);
+        ProfScope prof(PROF_DH_MERGE, stream);
+        hipLaunchKernelGGL((dh_merge_kernel<D>), dim3((unsigned)((a_dh.N + PPB - 1) / PPB)), dim3(256), 0, stream, a_dh);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
 }  // namespace
 
 template <int D>
@@ -1343,6 +1484,18 @@ hipError_t launch_prep(const PrepArgs &p, hipStream_t stream)
     hipLaunchKernelGGL(prep_kernel, dim3((unsigned)((p.N + kPrepThreads - 1) / kPrepThreads)), dim3(kPrepThreads), 0,
                        stream, p);
     return hipGetLastError();
+}
+
+bool tile_backward_fusable(int d) { return d == 64 || d == 128; }
+
+hipError_t launch_tile_backward(const TileArgs &a_dh, const TileArgs &a_de, hipStream_t stream)
+{
+    if (a_dh.N == 0) return hipSuccess;
+    switch (a_dh.d) {
+    case 64: return launch_bwd_for_d<64>(a_dh, a_de, stream);
+    case 128: return launch_bwd_for_d<128>(a_dh, a_de, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream)
