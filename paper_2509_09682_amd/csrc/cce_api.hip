@@ -357,8 +357,8 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     p.skip_pos_dE = scatter ? 1 : 0;
     p.coef = reinterpret_cast<float *>(ws + L.coef);
     if (cce::launch_gather(true, bf16, p, stream) != hipSuccess) return CCE_ERR_HIP;
+    cce::TileArgs t{};
     if (scatter) {
-        cce::TileArgs t{};
         t.H = static_cast<const uint16_t *>(H);
         t.tgt = tgt;
         t.pos_mask = mask;
@@ -368,7 +368,6 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
         t.V = desc->V;
         t.d = desc->d;
         t.validate = desc->validate_indices ? 1 : 0;
-        if (cce::launch_pos_scatter(t, stream) != hipSuccess) return CCE_ERR_HIP;
     }
     cce::InvertArgs ia{};
     ia.H = H;
@@ -390,7 +389,7 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     ia.K = desc->K;
     ia.collide = desc->mask_target_collisions ? 1 : 0;
     ia.validate = desc->validate_indices ? 1 : 0;
-    return cce::launch_inverted_dE(bf16, ia, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+    return cce::launch_inverted_dE(bf16, ia, scatter ? &t : nullptr, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 
 cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream)

@@ -9,6 +9,7 @@
 // The correct items (power-law hot rows) are not part of the index: the aggregated scatter adds them.
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
+#include "cce_scatter.hpp"
 
 namespace cce {
 namespace {
@@ -133,35 +134,72 @@ constexpr int kBucketIds = 1 << kBucketShift;  // LDS histogram of level 2: 8 Ki
 constexpr int kMaxBuckets = 2048;               // LDS histogram of level 1: 8 KiB
 constexpr int kChunkPairs = 8192;               // pairs per block in level 1
 
+// The pairs of a block's chunk, kPairBatch per thread at a time: all mask bytes are requested first, then ids and
+// targets of the valid positions only (entries of padded positions are never read), so a thread waits for two round
+// trips per batch instead of three per pair.  Fewer than 2^31 pairs on this path: 32-bit pair arithmetic.
+constexpr int kPairBatch = 8;
+static_assert(kChunkPairs % (kThreads * kPairBatch) == 0, "whole batches per chunk");
+
+template <typename F>
+__device__ __forceinline__ void for_live_pairs(const InvertArgs &a, int64_t chunk, F &&visit)
+{
+    const uint32_t p0 = (uint32_t)chunk * kChunkPairs, total = (uint32_t)(a.N * a.K), K = (uint32_t)a.K;
+    for (int u0 = threadIdx.x; u0 < kChunkPairs; u0 += kThreads * kPairBatch) {
+        uint32_t pos[kPairBatch];
+        bool live[kPairBatch];
+        int32_t id[kPairBatch], ti[kPairBatch];
+#pragma unroll
+        for (int j = 0; j < kPairBatch; ++j) {
+            const uint32_t pair = p0 + u0 + j * kThreads;
+            pos[j] = pair / K;
+            live[j] = pair < total && (a.mask == nullptr || a.mask[pos[j]] != 0);
+        }
+#pragma unroll
+        for (int j = 0; j < kPairBatch; ++j) {
+            id[j] = ti[j] = 0;
+            if (live[j]) {
+                id[j] = a.neg[p0 + u0 + j * kThreads];
+                ti[j] = a.tgt[pos[j]];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kPairBatch; ++j) {
+            if (a.validate && (ti[j] < 0 || (int64_t)ti[j] >= a.V || id[j] < 0 || (int64_t)id[j] >= a.V)) live[j] = false;  // flagged elsewhere
+            if (a.collide && id[j] == ti[j]) live[j] = false;
+            if (live[j]) visit(id[j], (int32_t)pos[j]);
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void part_count_kernel(InvertArgs a)
 {
     __shared__ int32_t hist[kMaxBuckets];
     for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) hist[b] = 0;
     __syncthreads();
-    const int64_t p0 = (int64_t)blockIdx.x * kChunkPairs, total = a.N * a.K;
-    for (int u = threadIdx.x; u < kChunkPairs; u += kThreads) {
-        const int64_t pair = p0 + u;
-        int32_t id;
-        if (pair < total && pair_live(a, pair, id)) atomicAdd(&hist[id >> kBucketShift], 1);
-    }
+    for_live_pairs(a, (int64_t)blockIdx.x, [&](int32_t id, int32_t) { atomicAdd(&hist[id >> kBucketShift], 1); });
     __syncthreads();
     for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) a.part_hist[(int64_t)b * gridDim.x + blockIdx.x] = hist[b];
 }
 
-__global__ __launch_bounds__(kThreads) void part_scatter_kernel(InvertArgs a)
+// D_SC != 0: the first sc_blocks blocks scatter the gradient rows of the correct items (hidden size D_SC) instead;
+// nothing in this launch or the next reads or writes dE, and their latency hides under the filing of the pairs.
+template <int D_SC>
+__global__ __launch_bounds__(kThreads) void part_scatter_kernel(InvertArgs a, TileArgs sc, int64_t sc_blocks)
 {
     __shared__ int32_t cur[kMaxBuckets];
-    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) cur[b] = a.part_hist[(int64_t)b * gridDim.x + blockIdx.x];
-    __syncthreads();
-    const int64_t p0 = (int64_t)blockIdx.x * kChunkPairs, total = a.N * a.K;
-    for (int u = threadIdx.x; u < kChunkPairs; u += kThreads) {
-        const int64_t pair = p0 + u;
-        int32_t id;
-        if (pair < total && pair_live(a, pair, id)) {
-            const int32_t slot = atomicAdd(&cur[id >> kBucketShift], 1);
-            a.tmp[slot] = make_int2(id, (int32_t)(pair / a.K));
-        }
+    static_assert(kThreads == kPosChunk && kMaxBuckets * 4 >= kPosChunk * 8, "the scatter role sorts 256 keys in this array");
+    if (D_SC != 0 && (int64_t)blockIdx.x < sc_blocks) {
+        pos_scatter_block<(D_SC != 0 ? D_SC : 64)>(sc, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(cur));
+        return;
     }
+    const int64_t chunk = (int64_t)blockIdx.x - (D_SC != 0 ? sc_blocks : 0);
+    const int64_t n_chunks = (int64_t)gridDim.x - (D_SC != 0 ? sc_blocks : 0);
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) cur[b] = a.part_hist[(int64_t)b * n_chunks + chunk];
+    __syncthreads();
+    for_live_pairs(a, chunk, [&](int32_t id, int32_t pos) {
+        const int32_t slot = atomicAdd(&cur[id >> kBucketShift], 1);
+        a.tmp[slot] = make_int2(id, pos);
+    });
 }
 
 __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
@@ -301,10 +339,11 @@ int64_t invert_part_blocks(int64_t N, int64_t K) { return (N * K + kChunkPairs -
 int64_t invert_buckets(int64_t V) { return (V + kBucketIds - 1) / kBucketIds; }
 bool invert_partitioned(int64_t V) { return invert_buckets(V) <= kMaxBuckets; }
 
-hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, hipStream_t stream)
+hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, const TileArgs *scatter, hipStream_t stream)
 {
     InvertArgs a = a_in;
-    if (a.N == 0 || a.K == 0) return hipSuccess;
+    if (a.N == 0) return hipSuccess;
+    if (a.K == 0) return scatter ? launch_pos_scatter(*scatter, stream) : hipSuccess;
     const int64_t pairs = a.N * a.K;
     hipError_t e;
     {
@@ -317,9 +356,21 @@ hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, hipStream_t str
             hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
             if ((e = launch_fill_zero(a.part_total, 1, stream)) != hipSuccess) return e;
             if ((e = launch_scan(a.part_hist, n_hist + 1, a.block_sums, stream)) != hipSuccess) return e;
-            hipLaunchKernelGGL(part_scatter_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+            if (scatter) {  // the correct items' rows ride at the head of this launch
+                const int64_t sc_blocks = (scatter->N + kPosChunk - 1) / kPosChunk;
+                const dim3 grid((unsigned)(a.n_part_blocks + sc_blocks));
+                switch (scatter->d) {
+                case 64: hipLaunchKernelGGL(part_scatter_kernel<64>, grid, dim3(kThreads), 0, stream, a, *scatter, sc_blocks); break;
+                case 128: hipLaunchKernelGGL(part_scatter_kernel<128>, grid, dim3(kThreads), 0, stream, a, *scatter, sc_blocks); break;
+                case 256: hipLaunchKernelGGL(part_scatter_kernel<256>, grid, dim3(kThreads), 0, stream, a, *scatter, sc_blocks); break;
+                default: return hipErrorInvalidValue;
+                }
+            } else {
+                hipLaunchKernelGGL(part_scatter_kernel<0>, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a, TileArgs{}, 0);
+            }
             hipLaunchKernelGGL(bucket_sort_kernel, dim3((unsigned)a.n_buckets), dim3(kScanThreads), 0, stream, a);
         } else {
+            if (scatter && (e = launch_pos_scatter(*scatter, stream)) != hipSuccess) return e;
             const unsigned pair_blocks = (unsigned)((pairs + kThreads - 1) / kThreads);
             if ((e = launch_fill_zero(a.cursor, (size_t)a.V, stream)) != hipSuccess) return e;
             hipLaunchKernelGGL(count_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);

@@ -79,7 +79,8 @@ size_t invert_scan_blocks(int64_t n);          // blocks of the scan over n word
 int64_t invert_part_blocks(int64_t N, int64_t K);
 int64_t invert_buckets(int64_t V);
 bool invert_partitioned(int64_t V);            // false: catalogue too large for the LDS bucket histogram, atomics are used
-hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a, hipStream_t stream);
+// scatter != nullptr: the correct items' gradient rows are scattered on the way (their blocks lead the second index pass)
+hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a, const TileArgs *scatter, hipStream_t stream);
 
 // Aggregated scatter of the correct items on its own (bf16 inputs, d in {64,128,256}): dE[tgt_i] += coef_i * H_i.
 hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream);
