@@ -235,6 +235,42 @@ def test_full_size_configs_against_full_oracle(idx):
     assert np.abs(out["dE"].astype(np.float64).sum(0)).max() <= 1e-3 * scale, errs
 
 
+def test_item_table_beyond_4_gib_uses_64_bit_load_addresses():
+    """The tile kernels address streamed rows with 32-bit offsets below 4 GiB and with 64-bit addresses above:
+    a 4.4 GB item table with negatives spread over all of it takes the second path."""
+    import torch
+
+    import paper_2509_09682_amd as P
+    from hip_harness import to_device
+
+    w = make_workload("tile_wide_table", 6, 200, 256, 8_600_000, 300, "bf16", NEG_SHARED, 31337, pad="right", pad_len_lo=120,
+                      g_kind="random", e_sigma=0.05, tgt_dist="uniform")
+    assert int(w.V) * w.d * 2 > 2 ** 32 and int(w.neg.max()) * w.d * 2 > 2 ** 32
+    H, E, tgt, neg, mask = to_device(w)
+    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_BF16, w.neg_mode, mask_target_collisions=w.mask_collisions, algo=P.CCE_ALGO_TILE)
+    ws = P.new_workspace(desc)
+    loss = torch.full((w.N,), float("nan"), device="cuda")
+    lse = torch.full((w.N,), float("nan"), device="cuda")
+    dH = torch.full((w.N, w.d), float("nan"), device="cuda")
+    dE = torch.zeros((w.V, w.d), device="cuda")
+    P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+    P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, torch.from_numpy(w.g).cuda(), dH, dE, ws)
+    torch.cuda.synchronize()
+    S = np.flatnonzero(w.mask).astype(np.int64)
+    ref = O.run_workload(w, sel=S, want_dE="compact")
+    e_loss = per_position_rel(loss.cpu().numpy()[S], ref.loss, ref.lse, ref.loss)
+    e_lse = per_position_rel(lse.cpu().numpy()[S], ref.loss, ref.lse, ref.lse)
+    e_dH = tensor_rel(dH.cpu().numpy()[S], ref.dH)
+    rows = torch.from_numpy(ref.dE_rows).cuda()
+    e_dE = tensor_rel(dE[rows].cpu().numpy(), ref.dE)
+    other = torch.ones(w.V, dtype=torch.bool, device="cuda")
+    other[rows] = False
+    assert float(dE[other].abs().max()) == 0.0
+    errs = dict(loss=e_loss, lse=e_lse, dH=e_dH, dE=e_dE)
+    print(w.name, {k: f"{v:.2e}" for k, v in errs.items()})
+    assert all(v <= TOL_BF16 for v in errs.values()), errs
+
+
 @pytest.mark.parametrize("idx,n_sample", [(4, 192), (5, 96)])
 def test_full_size_large_configs_on_sampled_positions(idx, n_sample):
     """The benchmark shapes the oracle cannot finish in seconds, in the launch configuration bench.py times.
