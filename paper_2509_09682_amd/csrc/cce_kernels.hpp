@@ -40,8 +40,8 @@ struct TileArgs {
     void *dH;
     float *dE;
     float *coef;                 // [N] coefficient of the correct item, written by the dH pass, read by the scatter
-    uint32_t *de_const;          // [2, N] per compacted position: exponent offset (float bits) and sign of the dE
-                                 // coefficient, written by the dH pass, streamed by the dE pass
+    uint32_t *de_const;          // [2, N] per compacted position (float bits): exponent offset -lse log2e and upstream
+                                 // gradient g of the dE coefficient; written ahead of the dE pass, streamed by it
     float *part_m, *part_s;      // [splits, N] partial max / sum of split forward runs
     float *part_dH;              // [splits, N, d] partial dH of split runs
     int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode

@@ -283,12 +283,12 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         cx[g] = 0.f;
         if (MODE == MODE_DH) {
             cx[g] = -a.lse_in[xrow[g]] * kLog2e;
-            // The dE pass wants g * exp(o - lse) = sign(g) * 2^(o log2e - lse log2e + log2|g|) for every position it
-            // streams: offset and sign are filed here under the compacted index, where that pass finds them in order.
+            // The dE pass wants g * exp(o - lse) = g * 2^(o log2e - lse log2e) for every position it streams: the
+            // offset and g are filed here under the compacted index, where that pass finds them in order.
             if (a.write_consts && split == 0 && hi == 0 && half == 0 && x_ok[g]) {
                 const float gg = a.g ? a.g[xrow[g]] : 1.f;
-                a.de_const[x] = __float_as_uint(cx[g] + __builtin_amdgcn_logf(fabsf(gg)));
-                a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
+                a.de_const[x] = __float_as_uint(cx[g]);
+                a.de_const[a.N + x] = __float_as_uint(gg);
             }
         }
     }
@@ -466,7 +466,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             }
         } else {
             const float *yc = reinterpret_cast<const float *>(tile + OFF_C);
-            const uint32_t *ys = reinterpret_cast<const uint32_t *>(tile + OFF_C) + BY;
+            const float *yg = reinterpret_cast<const float *>(tile + OFF_C) + BY;
 #pragma unroll
             for (int g = 0; g < XG; ++g) {
                 float v[16];
@@ -477,11 +477,11 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 #pragma unroll
                     for (int qq = 0; qq < 4; ++qq) {
                         const float4 cy = *reinterpret_cast<const float4 *>(&yc[sb * 32 + qq * 8 + hi * 4]);
-                        const uint4 sg = *reinterpret_cast<const uint4 *>(&ys[sb * 32 + qq * 8 + hi * 4]);
-                        v[qq * 4 + 0] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 0], kLog2e, cy.x))) | sg.x);
-                        v[qq * 4 + 1] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 1], kLog2e, cy.y))) | sg.y);
-                        v[qq * 4 + 2] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 2], kLog2e, cy.z))) | sg.z);
-                        v[qq * 4 + 3] = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 3], kLog2e, cy.w))) | sg.w);
+                        const float4 gy = *reinterpret_cast<const float4 *>(&yg[sb * 32 + qq * 8 + hi * 4]);
+                        v[qq * 4 + 0] = gy.x * __builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 0], kLog2e, cy.x));
+                        v[qq * 4 + 1] = gy.y * __builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 1], kLog2e, cy.y));
+                        v[qq * 4 + 2] = gy.z * __builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 2], kLog2e, cy.z));
+                        v[qq * 4 + 3] = gy.w * __builtin_amdgcn_exp2f(fmaf(sv[g][qq * 4 + 3], kLog2e, cy.w));
                     }
                 }
                 if (RAGGED) {
@@ -906,8 +906,8 @@ __global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArg
 }
 
 // Per valid position, ahead of a fused backward launch: the coefficient of the correct item g (w p+ - 1) for the
-// scatter, and offset and sign of the dE coefficients g exp(o - lse) = sign(g) 2^(o log2e - lse log2e + log2|g|) under
-// the compacted index.  D/8 lanes per position share the scalar product with the correct item's row.
+// scatter, and the exponent offset -lse log2e and g of the dE coefficients g exp(o - lse) = g 2^(o log2e - lse log2e)
+// under the compacted index.  D/8 lanes per position share the scalar product with the correct item's row.
 template <int D>
 __global__ __launch_bounds__(256) void bwd_pre_kernel(TileArgs a)
 {
@@ -933,8 +933,8 @@ __global__ __launch_bounds__(256) void bwd_pre_kernel(TileArgs a)
         const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[row] : 1.f);
         const float gg = a.g ? a.g[row] : 1.f;
         a.coef[row] = gg * (w * __builtin_amdgcn_exp2f(fmaf(op, kLog2e, nl)) - 1.f);
-        a.de_const[x] = __float_as_uint(nl + __builtin_amdgcn_logf(fabsf(gg)));
-        a.de_const[a.N + x] = __float_as_uint(gg) & 0x80000000u;
+        a.de_const[x] = __float_as_uint(nl);
+        a.de_const[a.N + x] = __float_as_uint(gg);
     }
 }
 
