@@ -37,6 +37,16 @@
  *     contribution, and their ids are never read;
  *   - K = 0 gives loss = 0 and zero gradients (p of the only candidate is 1).
  *
+ * Gradient filtering (Sec. 3.1, last paragraph: computations with values below a
+ * prescribed threshold are disregarded in the backward pass; Sec. 3.3 notes that it
+ * can follow step 4 of Alg. 2; Sec. 4.3 sweeps the threshold filter_eps).  The paper
+ * gives no granularity.  Reading taken here: the softmax matrix of the valid
+ * positions (batch order) by the candidates (catalogue order) is cut into square
+ * blocks of `block` entries a side, aligned at the origin; a block whose largest
+ * probability is below filter_eps is taken as zero in Eq. 6, the subtraction of
+ * the one-hot target stays.  loss and lse are not touched.  cce_oracle_filter_blocks
+ * marks the surviving entries, cce_oracle_run applies the marks (p_keep).
+ *
  * Parity pins: the tests under tests/ (marker "not gpu") check this file against
  * brute-force full softmax, the K = V-1 full-catalogue identity, central finite
  * differences, closed forms (H = 0, dominant score), softmax rows summing to 1,
@@ -87,6 +97,9 @@ int cce_oracle_num_threads(void)
  *   p_out     : [n_out, n_cand] softmax values (0 for dead candidates), optional;
  *               n_cand = K+1 for the sampled modes, V for the full catalogue
  *   g         : [N] upstream gradient per position, NULL = 1
+ *   p_keep    : [n_out, n_cand] bytes, optional: where 0, the softmax value counts
+ *               as zero in the gradients (gradient filtering); p_out still holds
+ *               the unfiltered softmax
  *
  * Returns 0, 1 (bad argument), 2 (id out of range), 3 (missing dE slot).
  */
@@ -94,7 +107,7 @@ int cce_oracle_run(int64_t N, int64_t V, int32_t d, int32_t K, int32_t in_dtype,
                    int32_t mask_collisions, const void *H, const void *E, const int32_t *tgt,
                    const int32_t *neg, const uint8_t *mask, const double *g, int64_t n_sel,
                    const int64_t *sel, double *loss, double *lse, double *dH, const int64_t *row_slot,
-                   double *dE, double *p_out)
+                   double *dE, double *p_out, const uint8_t *p_keep)
 {
     if (N < 0 || V <= 0 || d <= 0 || K < 0 || !H || !E || !tgt || !loss || !lse)
         return 1;
@@ -194,7 +207,8 @@ int cce_oracle_run(int64_t N, int64_t V, int32_t d, int32_t K, int32_t in_dtype,
                     p_out[r * n_cand + j] = p;
                 if (!live[j])
                     continue;
-                const double G = gi * (p - (j == pos ? 1.0 : 0.0));
+                const double pf = (p_keep && !p_keep[r * n_cand + j]) ? 0.0 : p; /* filtered block: taken as zero */
+                const double G = gi * (pf - (j == pos ? 1.0 : 0.0));
                 if (dH)
                     for (int t = 0; t < d; ++t)
                         dh[t] += G * load_elem(E, in_dtype, cand[j] * (int64_t)d + t);
@@ -226,4 +240,31 @@ int cce_oracle_run(int64_t N, int64_t V, int32_t d, int32_t K, int32_t in_dtype,
         free(live);
     }
     return status;
+}
+
+/*
+ * Gradient filtering, block reading (see the header): p is the [n_rows, n_cand]
+ * softmax of the VALID positions in batch order.  keep[r, j] = 1 iff the block
+ * (r / block, j / block) holds at least one probability >= eps.
+ * Returns 0, or 1 for a bad argument.
+ */
+int cce_oracle_filter_blocks(int64_t n_rows, int64_t n_cand, int32_t block, double eps, const double *p, uint8_t *keep)
+{
+    if (n_rows < 0 || n_cand <= 0 || block <= 0 || !p || !keep)
+        return 1;
+    for (int64_t r0 = 0; r0 < n_rows; r0 += block)
+        for (int64_t j0 = 0; j0 < n_cand; j0 += block) {
+            const int64_t r1 = r0 + block < n_rows ? r0 + block : n_rows;
+            const int64_t j1 = j0 + block < n_cand ? j0 + block : n_cand;
+            double big = 0.0;
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t j = j0; j < j1; ++j)
+                    if (p[r * n_cand + j] > big)
+                        big = p[r * n_cand + j];
+            const uint8_t k = (big >= eps) ? 1 : 0;
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t j = j0; j < j1; ++j)
+                    keep[r * n_cand + j] = k;
+        }
+    return 0;
 }

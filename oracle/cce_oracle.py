@@ -32,8 +32,11 @@ def _lib():
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ]
+        lib.cce_oracle_filter_blocks.restype = ctypes.c_int
+        lib.cce_oracle_filter_blocks.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                                 ctypes.c_void_p, ctypes.c_void_p]
         lib.cce_oracle_num_threads.restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -91,10 +94,11 @@ def touched_rows(tgt, neg, mask, neg_mode: int, V: int, sel=None, mask_collision
 
 
 def run(H, E, tgt, neg, mask, g, *, in_dtype: str, neg_mode: int, mask_collisions: int = 1, K: Optional[int] = None,
-        sel=None, want_dH: bool = True, want_dE: str = "dense", want_p: bool = False) -> OracleResult:
+        sel=None, want_dH: bool = True, want_dE: str = "dense", want_p: bool = False, p_keep=None) -> OracleResult:
     """H, E: float32 arrays (in_dtype 'f32') or uint16 bf16 bit patterns ('bf16').
 
     want_dE: "none" | "dense" ([V,d]) | "compact" (rows = touched_rows(...)).
+    p_keep: optional [n_out, n_cand] uint8 marks of the gradient filter (filter_blocks).
     """
     lib = _lib()
     H = np.ascontiguousarray(H)
@@ -135,9 +139,13 @@ def run(H, E, tgt, neg, mask, g, *, in_dtype: str, neg_mode: int, mask_collision
     elif want_dE != "none":
         raise ValueError(want_dE)
 
+    keep_a = None
+    if p_keep is not None:
+        keep_a = np.ascontiguousarray(p_keep, dtype=np.uint8)
+        assert keep_a.shape == (n_out, n_cand)
     rc = lib.cce_oracle_run(N, V, d, K_, dt, neg_mode, int(mask_collisions), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg_a),
                             _ptr(mask_a), _ptr(g_a), n_out, _ptr(sel_a), _ptr(loss), _ptr(lse), _ptr(dH), _ptr(slot),
-                            _ptr(dE), _ptr(p))
+                            _ptr(dE), _ptr(p), _ptr(keep_a))
     if rc != 0:
         raise RuntimeError(f"cce_oracle_run failed with status {rc}")
     return OracleResult(loss, lse, dH, dE, rows, p)
@@ -147,3 +155,24 @@ def run_workload(w, *, g=None, sel=None, want_dE: str = "dense", want_p: bool = 
     """Convenience: run on a workloads.Workload."""
     return run(w.H, w.E, w.tgt, w.neg, w.mask, w.g if g is None else g, in_dtype=w.in_dtype, neg_mode=w.neg_mode,
                mask_collisions=w.mask_collisions, K=w.K, sel=sel, want_dH=want_dH, want_dE=want_dE, want_p=want_p)
+
+
+def filter_blocks(p: np.ndarray, eps: float, block: int = 32) -> np.ndarray:
+    """Marks of the gradient filter for the softmax p [n_valid, n_cand] of the valid positions in batch order."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    keep = np.zeros(p.shape, np.uint8)
+    rc = _lib().cce_oracle_filter_blocks(p.shape[0], p.shape[1], int(block), float(eps), _ptr(p), _ptr(keep))
+    if rc != 0:
+        raise RuntimeError(f"cce_oracle_filter_blocks failed with status {rc}")
+    return keep
+
+
+def run_workload_filtered(w, eps: float, *, g=None, block: int = 32, want_dE: str = "dense"):
+    """Forward + filtered backward on a workload.  Returns (result over the valid positions in batch order, their
+    indices, the unfiltered softmax of those positions)."""
+    valid = np.flatnonzero(np.asarray(w.mask) != 0).astype(np.int64)
+    first = run_workload(w, g=g, sel=valid, want_dE="none", want_p=True, want_dH=False)
+    keep = filter_blocks(first.p, eps, block)
+    res = run(w.H, w.E, w.tgt, w.neg, w.mask, w.g if g is None else g, in_dtype=w.in_dtype, neg_mode=w.neg_mode,
+              mask_collisions=w.mask_collisions, K=w.K, sel=valid, want_dE=want_dE, p_keep=keep)
+    return res, valid, first.p

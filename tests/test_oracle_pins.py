@@ -334,3 +334,73 @@ def test_bf16_inputs_are_widened_exactly():
     # the rounding helper itself: round-to-nearest-even on the 16 dropped bits
     x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.140625], np.float32)  # 1+2^-8 ties to even (1.0); 1+3*2^-8 ties up
     assert np.array_equal(f32_from_bf16_bits(bf16_bits_from_f32(x)), np.array([1.0, 1.0, 1.015625, -2.5, 3.140625], np.float32))
+
+
+# ---- P11: gradient filtering (block reading) -------------------------------------------------------------------
+def _peaked_full_case(seed, N=70, V=150, d=8, frac_masked=0.2):
+    """Full-catalogue case whose softmax is concentrated: hidden states point at their target's row."""
+    r = np.random.default_rng(seed)
+    E = r.standard_normal((V, d)).astype(np.float32)
+    tgt = r.integers(0, V, N).astype(np.int32)
+    H = (2.5 * E[tgt] + 0.3 * r.standard_normal((N, d))).astype(np.float32)
+    mask = (r.random(N) >= frac_masked).astype(np.uint8)
+    g = r.standard_normal(N)
+    return H, E, tgt, mask, g
+
+
+def test_filter_with_zero_threshold_changes_nothing_and_with_huge_threshold_leaves_the_one_hot_term():
+    H, E, tgt, mask, g = _peaked_full_case(5)
+    valid = np.flatnonzero(mask).astype(np.int64)
+    base = O.run(H, E, tgt, None, mask, g, in_dtype="f32", neg_mode=FULL, sel=valid, want_p=True)
+    keep_all = O.filter_blocks(base.p, 0.0, 32)
+    assert keep_all.all()
+    same = O.run(H, E, tgt, None, mask, g, in_dtype="f32", neg_mode=FULL, sel=valid, p_keep=keep_all)
+    assert np.array_equal(same.dH, base.dH) and np.array_equal(same.loss, base.loss)
+    np.testing.assert_allclose(same.dE, base.dE, rtol=1e-13, atol=1e-15)   # threads add in any order
+    none = O.filter_blocks(base.p, 2.0, 32)          # no probability reaches 2
+    assert not none.any()
+    only = O.run(H, E, tgt, None, mask, g, in_dtype="f32", neg_mode=FULL, sel=valid, p_keep=none)
+    # closed form: G = -g on the target column only; loss and lse are those of the unfiltered run
+    assert np.array_equal(only.loss, base.loss) and np.array_equal(only.lse, base.lse)
+    np.testing.assert_allclose(only.dH, -g[valid, None] * E[tgt[valid]].astype(np.float64), rtol=1e-13, atol=1e-13)
+    dE = np.zeros((E.shape[0], E.shape[1]))
+    np.add.at(dE, tgt[valid], -g[valid, None] * H[valid].astype(np.float64))
+    np.testing.assert_allclose(only.dE, dE, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("block,eps", [(8, 1e-2), (8, 0.2), (16, 0.9)])
+def test_filter_against_dense_matrix_products(block, eps):
+    """Library routines on materialised matrices: scipy softmax, block maxima by reshaping a padded copy, and the
+    gradients as two matrix products with the filtered softmax."""
+    from scipy.special import softmax
+
+    H, E, tgt, mask, g = _peaked_full_case(11)
+    valid = np.flatnonzero(mask)
+    Hv, gv, tv = H[valid].astype(np.float64), g[valid], tgt[valid]
+    P = softmax(Hv @ E.astype(np.float64).T, axis=1)
+    nr, nc = P.shape
+    pr, pc = -nr % block, -nc % block
+    big = np.pad(P, ((0, pr), (0, pc))).reshape((nr + pr) // block, block, (nc + pc) // block, block).max(axis=(1, 3))
+    keep = np.repeat(np.repeat(big >= eps, block, axis=0), block, axis=1)[:nr, :nc]
+    assert 0 < keep.mean() < 1                       # the case exercises both outcomes
+    Pf = np.where(keep, P, 0.0)
+    Y = np.zeros_like(P)
+    Y[np.arange(nr), tv] = 1.0
+    G = gv[:, None] * (Pf - Y)
+    got, sel, p = _filtered(H, E, tgt, mask, g, eps, block)
+    assert np.array_equal(sel, valid)
+    np.testing.assert_allclose(p, P, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(got.dH, G @ E.astype(np.float64), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(got.dE, G.T @ Hv, rtol=1e-11, atol=1e-12)
+    # every dropped probability is below the threshold, every probability at or above it survives
+    marks = O.filter_blocks(p, eps, block).astype(bool)
+    assert np.array_equal(marks, keep) and (p[~marks] < eps).all() and marks[p >= eps].all()
+
+
+def _filtered(H, E, tgt, mask, g, eps, block):
+    class W:  # the few fields run_workload_filtered reads
+        pass
+    w = W()
+    w.H, w.E, w.tgt, w.neg, w.mask, w.g = H, E, tgt, None, mask, g
+    w.in_dtype, w.neg_mode, w.mask_collisions, w.K = "f32", FULL, 1, 0
+    return O.run_workload_filtered(w, eps, block=block)
