@@ -121,6 +121,8 @@ def main() -> int:
     ap.add_argument("--algo", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold-reps", type=int, default=5, help="steps timed with a 1 GiB cache-evicting write in front (0 = skip)")
+    ap.add_argument("--filter-eps", type=float, default=0.0, help="gradient filtering threshold (full-catalogue workload c4 only)")
+    ap.add_argument("--peaked", action="store_true", help="hidden states that point at their target row: a concentrated softmax, as late in training (c4)")
     ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes the padding compaction of the forward call")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
@@ -152,6 +154,13 @@ def main() -> int:
     from workloads import config
 
     w = config(args.config)
+    if args.peaked:
+        from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+        rng = np.random.default_rng(7)
+        Ef = f32_from_bf16_bits(w.E)
+        scale = 9.0 / float(np.mean(np.sum(Ef * Ef, axis=1)))   # correct-item score about 9 above the rest
+        w.H = bf16_bits_from_f32((scale * Ef[w.tgt] + 0.5 * rng.standard_normal((w.N, w.d)).astype(np.float32)).astype(np.float32))
+        w.name += "_peaked"
     H, E, tgt, neg, mask = to_device(w)
     algo = {"auto": P.CCE_ALGO_AUTO, "gather": P.CCE_ALGO_GATHER, "tile": P.CCE_ALGO_TILE}[args.algo]
     desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
@@ -160,7 +169,7 @@ def main() -> int:
     # the backward call may then reuse the forward call's compaction of the padded positions
     desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
                            mask_target_collisions=w.mask_collisions, validate_indices=0, algo=algo,
-                           reuse_forward_prep=0 if args.no_reuse_prep else 1)
+                           reuse_forward_prep=0 if args.no_reuse_prep else 1, filter_eps=args.filter_eps)
     ws = P.new_workspace(desc)
     loss = torch.empty(w.N, device="cuda")
     lse = torch.empty(w.N, device="cuda")
@@ -260,7 +269,7 @@ def main() -> int:
         "config": {
             "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
             "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
-            "reuse_forward_prep": not args.no_reuse_prep,
+            "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": args.filter_eps,
             "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
             "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
             "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,

@@ -75,6 +75,13 @@ typedef struct {
                                        there (nothing else wrote to it since), so the compaction of padded positions
                                        and the collision counts are not recomputed.  0: no assumption.  With 1 and a
                                        workspace that does not hold them the results are undefined. */
+    float filter_eps;               /* backward only, gradient filtering of the full-catalogue mode (Sec. 3.1, last
+                                       paragraph; Sec. 4.3): 0 = off.  > 0: the softmax matrix of the valid positions
+                                       (batch order) by the items (id order) is cut into 32 x 32 blocks aligned at the
+                                       origin, and a block whose largest probability is below filter_eps counts as
+                                       zero in Eq. 6 (it adds nothing to dH or dE; the term of the correct item stays).
+                                       loss and lse are exact.  Needs CCE_NEG_FULL, bf16 inputs and d in {64,128,256},
+                                       else CCE_ERR_UNSUPPORTED; negative or NaN: CCE_ERR_SHAPE. */
 } cce_desc;
 
 /* Bytes of device workspace both calls need for this descriptor.  Returns 0 for an invalid descriptor.

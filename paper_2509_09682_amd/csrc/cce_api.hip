@@ -1,5 +1,6 @@
 // C ABI of the CCE- library: argument checks, workspace layout, dispatch.  See include/cce_neg.h for the contract.
 #include <hip/hip_runtime.h>
+#include <math.h>
 
 #include <string.h>
 #include <vector>
@@ -94,6 +95,8 @@ cce_status check_desc(const cce_desc *d)
     if (d->dH_dtype == CCE_BF16 && d->in_dtype != CCE_BF16) return CCE_ERR_DTYPE;
     if (d->algo != CCE_ALGO_AUTO && d->algo != CCE_ALGO_GATHER && d->algo != CCE_ALGO_TILE) return CCE_ERR_UNSUPPORTED;
     if (d->algo == CCE_ALGO_TILE && !tile_eligible(d)) return CCE_ERR_UNSUPPORTED;
+    if (!(d->filter_eps >= 0.f)) return CCE_ERR_SHAPE;  // negative or NaN
+    if (d->filter_eps > 0.f && !(d->neg_mode == CCE_NEG_FULL && use_tile(d))) return CCE_ERR_UNSUPPORTED;
     return CCE_OK;
 }
 
@@ -331,6 +334,7 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
         a.dH = dH;
         a.dE = dE;
         a.write_consts = 1;
+        a.filter_log2 = desc->filter_eps > 0.f ? log2f(desc->filter_eps) : -INFINITY;
         cce::TileArgs a_de = a;
         a_de.splits = L.splits_de;
         if (cce::tile_backward_fusable(desc->d))  // both passes in one launch, behind a small per-position pass

@@ -49,6 +49,7 @@ struct TileArgs {
     int64_t pad_blocks;          // dH launch: blocks [0, pad_blocks) zero the dH rows of padded positions (set by the launcher)
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
     int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
+    float filter_log2;           // backward, gradient filtering: log2 of the threshold; -inf = off
 };
 
 enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items

@@ -156,6 +156,7 @@ __device__ __forceinline__ float max3_after(float after, float x, float y, float
 // wavefront (XG = 2 reads every streamed operand from LDS once for two matrix instructions).  MINB: blocks per
 // compute unit the register budget is sized for.  NBUF: LDS tile buffers in the ring (2..4: separate arrays, main loop
 // unrolled NBUF times, NBUF - 1 tiles in flight; 0: two buffers in one array and a single copy of the loop body).
+// FILTER: gradient filtering of the backward passes (32 x 32 blocks of the softmax matrix below a threshold are skipped).
 // DS: wavefronts that share a group of stationary rows in the backward passes; each of them forms the full score tile
 // and keeps 1/DS of the output columns, which divides the accumulator registers by DS at the price of DS score products.
 // LDS needs of one tile-kernel configuration (the kernel wrappers declare the arrays, the body gets pointers).
@@ -175,7 +176,7 @@ struct TileGeom {
     static constexpr int EPI_OWN = (MODE == MODE_DE && !EPI_IN_TILES) ? EPI_BYTES / 4 : 4;  // floats
 };
 
-template <int D, int MODE, int BY, int NW, int XG, int NBUF, int DS>
+template <int D, int MODE, int BY, int NW, int XG, int NBUF, int DS, bool FILTER = false>
 __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_id, uint16_t *const buf0, uint16_t *const buf1,
                                           uint16_t *const buf2, uint16_t *const buf3, float *const epi_own)
 {
@@ -437,7 +438,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[kk]), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
     };
     // accumulator register q of lane (lo, hi) holds streamed row y = sb*32 + (q/4)*8 + hi*4 + q%4
-    auto softmax = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG], gp_t &gp, int rows_here, auto ragged_tag) {
+    auto softmax = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG], gp_t &gp, int rows_here, auto ragged_tag, bool &kept) {
         constexpr bool RAGGED = decltype(ragged_tag)::value;
         const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
         if (MODE == MODE_FWD) {
@@ -467,6 +468,60 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         } else {
             const float *yc = reinterpret_cast<const float *>(tile + OFF_C);
             const float *yg = reinterpret_cast<const float *>(tile + OFF_C) + BY;
+            if constexpr (FILTER) {
+                // Gradient filtering: this wavefront's 32 stationary rows by the 32 streamed rows of the sub-tile are one
+                // block of the softmax matrix (both passes cut it the same way: positions by 32 in compacted order,
+                // items by 32 in id order).  Its probabilities are 2^a with a = o log2e - lse log2e; if none reaches the
+                // threshold the block contributes nothing, and neither exponentials nor the second product are spent.
+                kept = false;
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    float lg[16];
+                    float4 gy[4];
+                    if (MODE == MODE_DH) {
+#pragma unroll
+                        for (int q = 0; q < 16; ++q) lg[q] = fmaf(sv[g][q], kLog2e, cx[g]);
+                    } else {
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq) {
+                            const float4 cy = *reinterpret_cast<const float4 *>(&yc[sb * 32 + qq * 8 + hi * 4]);
+                            gy[qq] = *reinterpret_cast<const float4 *>(&yg[sb * 32 + qq * 8 + hi * 4]);
+                            lg[qq * 4 + 0] = fmaf(sv[g][qq * 4 + 0], kLog2e, cy.x);
+                            lg[qq * 4 + 1] = fmaf(sv[g][qq * 4 + 1], kLog2e, cy.y);
+                            lg[qq * 4 + 2] = fmaf(sv[g][qq * 4 + 2], kLog2e, cy.z);
+                            lg[qq * 4 + 3] = fmaf(sv[g][qq * 4 + 3], kLog2e, cy.w);
+                        }
+                    }
+                    if (RAGGED) {
+#pragma unroll
+                        for (int q = 0; q < 16; ++q)
+                            if ((q / 4) * 8 + (q % 4) >= rem) lg[q] = -INFINITY;
+                    }
+                    float big = max3(lg[0], lg[1], lg[2]);
+#pragma unroll
+                    for (int q = 3; q < 15; q += 2) big = max3(big, lg[q], lg[q + 1]);
+                    big = fmaxf(big, lg[15]);
+                    // stationary rows past the end hold a copy of row 0: they must not keep a block alive
+                    const bool keep_g = __any(x_ok[g] && big >= a.filter_log2);
+                    if (keep_g) {
+#pragma unroll
+                        for (int q = 0; q < 16; q += 2) {
+                            float v0 = __builtin_amdgcn_exp2f(lg[q]), v1 = __builtin_amdgcn_exp2f(lg[q + 1]);
+                            if (MODE == MODE_DE) {
+                                const float4 &gq = gy[q / 4];
+                                v0 *= (q % 4 == 0) ? gq.x : gq.z;
+                                v1 *= (q % 4 == 0) ? gq.y : gq.w;
+                            }
+                            gp[g][q / 2] = pack2(v0, v1);
+                        }
+                        kept = true;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) gp[g][q] = 0u;
+                    }
+                }
+                return;
+            }
 #pragma unroll
             for (int g = 0; g < XG; ++g) {
                 float v[16];
@@ -546,6 +601,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             f32x16 sv[2][XG];
             gp_t gp[2];
             s16x8 tr[2][MBH];
+            bool kept[2] = {true, true};  // gradient filtering: whether the sub-tile of either register set survived
             // Forward: operands two sub-tiles ahead (nothing else covers their latency).  Backward: one ahead, and the
             // second product of the previous sub-tile goes to the matrix pipe before the score product that needs them.
             constexpr int OPD = BWD ? 1 : 2;
@@ -559,10 +615,10 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 const int c = k & 1, n = c ^ 1;
                 const int opn = (OPD == 2) ? n : 0, opl = (OPD == 2) ? c : 0;  // set S(k+1) reads / set loaded now
                 if (k + OPD < NSB) load_ops(tile, k + OPD, op[opl]);
-                if (BWD && k > 0) second(tr, gp[n]);
+                if (BWD && k > 0 && kept[n]) second(tr, gp[n]);
                 if (k + 1 < NSB) mfma_scores(op[opn], sv[n]);
-                softmax(tile, k, sv[c], gp[c], rows_here, ragged_tag);
-                if (BWD) load_tr(tile, k, tr);
+                softmax(tile, k, sv[c], gp[c], rows_here, ragged_tag, kept[c]);
+                if (BWD && kept[c]) load_tr(tile, k, tr);
                 // ---- issue order of this phase
                 const int n_mfma = ((BWD && k > 0) ? NM_P : 0) + (k + 1 < NSB ? NM_S : 0);
                 if (k + OPD < NSB) __builtin_amdgcn_sched_group_barrier(0x100, KK, 0);
@@ -589,7 +645,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 }
                 if (BWD) __builtin_amdgcn_sched_group_barrier(0x100, N_TR, 0);
             }
-            if (BWD) {
+            if (BWD && kept[(NSB - 1) & 1]) {
                 second(tr, gp[(NSB - 1) & 1]);
                 __builtin_amdgcn_sched_group_barrier(0x008, NM_P, 0);
             }
@@ -648,11 +704,16 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                             dst[i] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
                         }
                     };
+                    bool kept = true;
+                    if (FILTER) {  // the reads wait for the verdict on the block
+                        softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
+                        if (!kept) continue;
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                     read_tr_batch(0, tb[0]);
                     read_tr_batch(1, tb[1]);
                     __builtin_amdgcn_sched_barrier(0);
-                    softmax(tile, sb, sv, gp, rows_here, ragged_tag);
+                    if (!FILTER) softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
 #pragma unroll
                     for (int b = 0; b < NB_P; ++b) {
                         __builtin_amdgcn_sched_barrier(0);
@@ -672,7 +733,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                         if (b + 2 < NB_P) read_tr_batch(b + 2, tb[b & 1]);
                     }
                 } else {
-                    softmax(tile, sb, sv, gp, rows_here, ragged_tag);
+                    bool kept = true;
+                    softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
                 }
             }
         }
@@ -867,7 +929,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     }
 }
 
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS>
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS, bool FILTER>
 __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 {
     typedef TileGeom<D, MODE, BY, NW, XG, NBUF, DS> G;
@@ -876,7 +938,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
     __shared__ __attribute__((aligned(1024))) uint16_t buf2[G::BUF2];
     __shared__ __attribute__((aligned(1024))) uint16_t buf3[G::BUF3];
     __shared__ __attribute__((aligned(16))) float epi_own[G::EPI_OWN];
-    tile_body<D, MODE, BY, NW, XG, NBUF, DS>(a, (int64_t)blockIdx.x, buf0, buf1, buf2, buf3, epi_own);
+    tile_body<D, MODE, BY, NW, XG, NBUF, DS, FILTER>(a, (int64_t)blockIdx.x, buf0, buf1, buf2, buf3, epi_own);
 }
 
 // The dH and the dE pass of one backward call in a single launch: with few positions neither pass fills the chip on
@@ -884,7 +946,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 // unit, so they overlap almost completely.  The dE blocks (correct-item scatter first) lead the grid, being the longer
 // ones.  Both roles share the LDS arrays; neither reads what the other writes (coef and de_const come from
 // bwd_pre_kernel).
-template <int D, int BY, int XG_DH, int XG_DE, int NBUF>
+template <int D, int BY, int XG_DH, int XG_DE, int NBUF, bool FILTER>
 __global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArgs a_de, int64_t de_blocks)
 {
     typedef TileGeom<D, MODE_DH, BY, 4, XG_DH, NBUF, 1> GH;
@@ -900,9 +962,9 @@ __global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArg
     // its tiles); measured faster on c2 than tiles first
     const int64_t b = (int64_t)blockIdx.x;
     if (b < de_blocks)
-        tile_body<D, MODE_DE, BY, 4, XG_DE, NBUF, 1>(a_de, b, buf0, buf1, buf2, buf3, epi_own);
+        tile_body<D, MODE_DE, BY, 4, XG_DE, NBUF, 1, FILTER>(a_de, b, buf0, buf1, buf2, buf3, epi_own);
     else
-        tile_body<D, MODE_DH, BY, 4, XG_DH, NBUF, 1>(a_dh, b - de_blocks, buf0, buf1, buf2, buf3, epi_own);
+        tile_body<D, MODE_DH, BY, 4, XG_DH, NBUF, 1, FILTER>(a_dh, b - de_blocks, buf0, buf1, buf2, buf3, epi_own);
 }
 
 // Per valid position, ahead of a fused backward launch: the coefficient of the correct item g (w p+ - 1) for the
@@ -1231,27 +1293,27 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
     return blocks;
 }
 
-template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1>
+template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1, bool FILTER = false>
 hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
 {
-    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>, NW * 64);
+    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>, NW * 64);
     const int64_t blocks = plan_tile_grid<MODE>(a, n_x, (NW / DS) * XG * 32, NW * 64, slots);
     if (blocks == 0) return hipSuccess;
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
-    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
+    hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
 
-template <int D, int XG_DH, int XG_DE>
+template <int D, int XG_DH, int XG_DE, bool FILTER = false>
 hipError_t launch_bwd_kernel(TileArgs &a_dh, TileArgs &a_de, hipStream_t stream)
 {
     constexpr int BY = 8192 / D, NBUF = 4;
-    static const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF>, 256);
+    static const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>, 256);
     const int64_t de_blocks = plan_tile_grid<MODE_DE>(a_de, a_de.n_cols, 4 * XG_DE * 32, 256, slots);
     const int64_t dh_blocks = plan_tile_grid<MODE_DH>(a_dh, a_dh.N, 4 * XG_DH * 32, 256, slots);
     if (de_blocks + dh_blocks == 0) return hipSuccess;
     ProfScope prof(PROF_TILE_BWD, stream);
-    hipLaunchKernelGGL((tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF>), dim3((unsigned)(de_blocks + dh_blocks)), dim3(256), 0, stream,
+    hipLaunchKernelGGL((tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>), dim3((unsigned)(de_blocks + dh_blocks)), dim3(256), 0, stream,
                        a_dh, a_de, de_blocks);
     return hipGetLastError();
 }
@@ -1307,7 +1369,10 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
                 done = true;
             }
         }
-        if (!done) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
+        if (!done && a.filter_log2 > -INFINITY) {
+            if constexpr (D > 128) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B, true>(a, a.N, stream);
+            else e = hipErrorInvalidValue;  // smaller hidden sizes filter in the fused launch
+        } else if (!done) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             ProfScope prof(PROF_DH_MERGE, stream);
@@ -1319,6 +1384,10 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     case TILE_PASS_DE:
         if constexpr (XG_B == 2) {
             if (wide(a.n_cols, false)) return launch_tile_kernel<D, MODE_DE, BY_B, 4, 2, MINB, NBUF_B>(a, a.n_cols, stream);
+        }
+        if (a.filter_log2 > -INFINITY) {
+            if constexpr (D > 128) return launch_tile_kernel<D, MODE_DE, BY_B, NW_L, 1, MINB, NBUF_B, DS_B, true>(a, a.n_cols, stream);
+            else return hipErrorInvalidValue;
         }
         return launch_tile_kernel<D, MODE_DE, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.n_cols, stream);
     default:
@@ -1344,7 +1413,9 @@ hipError_t launch_bwd_for_d(TileArgs a_dh, TileArgs a_de, hipStream_t stream)
     };
     const bool wide_dh = wide(a_dh.N, a_dh.splits, true), wide_de = wide(a_de.n_cols, a_de.splits, false);
     hipError_t e;
-    if constexpr (XG_B == 2) {
+    if (a_dh.filter_log2 > -INFINITY) {  // gradient filtering: one group of stationary rows per wavefront, so that a
+        e = launch_bwd_kernel<D, 1, 1, true>(a_dh, a_de, stream);  // dropped block skips a whole second product
+    } else if constexpr (XG_B == 2) {
         if (wide_dh && wide_de) e = launch_bwd_kernel<D, 2, 2>(a_dh, a_de, stream);
         else if (wide_dh) e = launch_bwd_kernel<D, 2, 1>(a_dh, a_de, stream);
         else if (wide_de) e = launch_bwd_kernel<D, 1, 2>(a_dh, a_de, stream);

@@ -80,3 +80,16 @@ def test_forward_backward_reject_null_and_small_workspace_before_launch(binding)
     assert st == B.CCE_ERR_DTYPE
     assert L.cce_neg_workspace_init(None, 4096, None) == B.CCE_ERR_NULL
     assert L.cce_neg_index_status(None, 4096, None) == B.CCE_ERR_NULL
+
+
+def test_gradient_filtering_is_accepted_only_where_it_is_defined(binding):
+    B = binding
+    ok = B.make_desc(256, 1000, 64, 0, B.CCE_BF16, B.CCE_NEG_FULL, filter_eps=1e-4)
+    assert B.cce_neg_workspace_bytes(ok) > 0
+    for kw in (dict(neg_mode=B.CCE_NEG_SHARED, K=64, in_dtype=B.CCE_BF16, d=64),   # sampled modes do not filter (Sec. 3.3)
+               dict(neg_mode=B.CCE_NEG_FULL, K=0, in_dtype=B.CCE_F32, d=64),       # fp32 runs on the row-gather path
+               dict(neg_mode=B.CCE_NEG_FULL, K=0, in_dtype=B.CCE_BF16, d=96)):     # no matrix-core kernel for this d
+        desc = B.make_desc(256, 1000, kw["d"], kw["K"], kw["in_dtype"], kw["neg_mode"], filter_eps=1e-4)
+        assert B.cce_neg_workspace_bytes(desc) == 0
+    for bad in (-1.0, float("nan")):
+        assert B.cce_neg_workspace_bytes(B.make_desc(256, 1000, 64, 0, B.CCE_BF16, B.CCE_NEG_FULL, filter_eps=bad)) == 0

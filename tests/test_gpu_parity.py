@@ -235,6 +235,54 @@ def test_full_size_configs_against_full_oracle(idx):
     assert np.abs(out["dE"].astype(np.float64).sum(0)).max() <= 1e-3 * scale, errs
 
 
+def _peaked_full_workload(d, V, seed):
+    """Full-catalogue workload with a concentrated softmax: hidden states point at their target's row."""
+    from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+
+    w = make_workload(f"filter_d{d}", 5, 77, d, V, 0, "bf16", NEG_FULL, seed, pad="bernoulli", pad_p=0.25, g_kind="random",
+                      e_sigma=1.0 / np.sqrt(d), tgt_dist="zipf")
+    rng = np.random.default_rng(seed + 1)
+    E = f32_from_bf16_bits(w.E)
+    H = 9.0 * E[w.tgt] + 0.5 * rng.standard_normal((w.N, d)).astype(np.float32)
+    w.H = bf16_bits_from_f32(H.astype(np.float32))
+    return w
+
+
+@pytest.mark.parametrize("d,V", [(64, 1500), (128, 700), (256, 900)])
+def test_gradient_filtering_of_the_full_catalogue_mode(d, V):
+    """filter_eps > 0: 32 x 32 blocks of the softmax matrix whose largest probability is below the threshold add nothing
+    to dH and dE; loss and lse stay exact.  Held against the oracle's block reading at a threshold that no block
+    maximum comes near (the two sides compute the probabilities in different precisions)."""
+    import paper_2509_09682_amd as P
+
+    w = _peaked_full_workload(d, V, 900 + d)
+    _, valid, p = O.run_workload_filtered(w, 1e-3)
+    # the threshold goes into the widest gap between block maxima around their median, so that about half of the blocks
+    # are dropped and every verdict is clear-cut
+    nr, nc = p.shape
+    big = np.pad(p, ((0, -nr % 32), (0, -nc % 32))).reshape((nr + -nr % 32) // 32, 32, (nc + -nc % 32) // 32, 32).max(axis=(1, 3))
+    srt = np.sort(big.ravel())
+    cand = srt[int(0.3 * srt.size):int(0.7 * srt.size)]
+    gaps = cand[1:] / cand[:-1]
+    k = int(np.argmax(gaps))
+    assert gaps[k] > 1.01
+    eps = float(np.sqrt(cand[k] * cand[k + 1]))
+    ref, valid, p = O.run_workload_filtered(w, eps)
+    dropped = 1.0 - O.filter_blocks(p, eps).mean()
+    assert 0.2 < dropped < 0.999, dropped            # most blocks go, some stay
+    out = _run(w, algo=P.CCE_ALGO_TILE, filter_eps=eps)
+    plain = _run(w, algo=P.CCE_ALGO_TILE)
+    assert np.array_equal(out["loss"], plain["loss"]) and np.array_equal(out["lse"], plain["lse"])   # forward untouched
+    assert np.all(out["dH"][w.mask == 0] == 0)
+    e_dH = tensor_rel(out["dH"][valid], ref.dH)
+    e_dE = tensor_rel(out["dE"], ref.dE)
+    # the filtered gradient differs from the exact one by more than the tolerance: the test can tell them apart
+    exact = O.run_workload(w)
+    d_dH = tensor_rel(exact.dH[valid], ref.dH)
+    print(w.name, f"eps {eps:.3e} dropped {dropped:.3f} dH {e_dH:.2e} dE {e_dE:.2e} (filtered vs exact oracle dH {d_dH:.2e})")
+    assert e_dH <= TOL_BF16 and e_dE <= TOL_BF16, (e_dH, e_dE)
+
+
 def test_item_table_beyond_4_gib_uses_64_bit_load_addresses():
     """The tile kernels address streamed rows with 32-bit offsets below 4 GiB and with 64-bit addresses above:
     a 4.4 GB item table with negatives spread over all of it takes the second path."""
