@@ -5,3 +5,4 @@ from .binding import (  # noqa: F401
     CCE_ERR_HIP, CceDesc, CceError, cce_neg_backward, cce_neg_forward, cce_neg_index_status,
     cce_neg_workspace_bytes, cce_neg_workspace_init, cce_neg_profile_enable, cce_neg_profile_read, make_desc, new_workspace, status_string,
 )
+from .autograd import cce_neg_loss  # noqa: F401,E402

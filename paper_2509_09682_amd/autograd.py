@@ -1,0 +1,87 @@
+"""torch.autograd front end of the C ABI: the loss as a differentiable function of the hidden states and the item table.
+
+Nothing of the method is computed here: forward() calls cce_neg_forward, backward() calls cce_neg_backward with the
+upstream gradient of the per-position loss vector (the paper's grad-LSE, Sec. 3.3), and the scalar reduction of Eq. 3
+is ordinary torch arithmetic on that vector, so its 1/N reaches the kernels through autograd as `grad_loss`.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+_workspaces: dict = {}
+_last_forward: dict = {}      # workspace key -> serial number of the forward call that filled it last
+_serial = 0
+
+
+def _workspace(desc: B.CceDesc, device):
+    """One workspace per descriptor shape and device; forward and backward of a step share it."""
+    key = (desc.N, desc.V, desc.d, desc.K, desc.in_dtype, desc.dH_dtype, desc.neg_mode, desc.mask_target_collisions,
+           desc.validate_indices, desc.algo, str(device))
+    ws = _workspaces.get(key)
+    if ws is None:
+        ws = _workspaces[key] = B.new_workspace(desc, device=device)
+    return key, ws
+
+
+class _CceNegLoss(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps):
+        if H.dtype != E.dtype or H.dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("H and E must both be float32 or both be bfloat16")
+        N, d = H.shape
+        V = E.shape[0]
+        K = 0 if neg is None or neg_mode == B.CCE_NEG_FULL else int(neg.shape[-1])
+        dt = B.CCE_F32 if H.dtype == torch.float32 else B.CCE_BF16
+        kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0)
+        desc = B.make_desc(N, V, d, K, dt, neg_mode, **kw)
+        global _serial
+        key, ws = _workspace(desc, H.device)
+        _serial += 1
+        _last_forward[key] = ctx.serial = _serial
+        ctx.key = key
+        H, E = H.contiguous(), E.contiguous()
+        loss = torch.empty(N, device=H.device, dtype=torch.float32)
+        lse = torch.empty(N, device=H.device, dtype=torch.float32)
+        B.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        ctx.save_for_backward(H, E, tgt, neg, mask, lse)
+        ctx.bwd = (N, V, d, K, dt, neg_mode, filter_eps, kw)
+        ctx.ws = ws
+        return loss
+
+    @staticmethod
+    def backward(ctx, grad_loss):
+        H, E, tgt, neg, mask, lse = ctx.saved_tensors
+        dH = torch.empty_like(H)
+        dE = torch.zeros(E.shape, device=E.device, dtype=torch.float32)   # the library accumulates into fp32
+        g = grad_loss.contiguous().to(torch.float32)
+        N, V, d, K, dt, neg_mode, filter_eps, kw = ctx.bwd
+        # the compaction the forward call left in the workspace is reused unless another forward call of the same
+        # shape has overwritten it since (two loss terms in one graph)
+        reuse = 1 if _last_forward.get(ctx.key) == ctx.serial else 0
+        desc = B.make_desc(N, V, d, K, dt, neg_mode, reuse_forward_prep=reuse, filter_eps=filter_eps, **kw)
+        B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE, ctx.ws)
+        return dH, dE.to(E.dtype), None, None, None, None, None, None
+
+
+def cce_neg_loss(H: torch.Tensor, E: torch.Tensor, tgt: torch.Tensor, neg: Optional[torch.Tensor] = None,
+                 mask: Optional[torch.Tensor] = None, *, neg_mode: int = B.CCE_NEG_SHARED, reduction: str = "mean",
+                 mask_target_collisions: bool = True, filter_eps: float = 0.0) -> torch.Tensor:
+    """Cross-entropy with negative sampling (Eq. 3-5), or over the full catalogue with neg_mode = CCE_NEG_FULL (Eq. 1-2).
+
+    H [N,d] hidden states, E [V,d] item table (both float32 or both bfloat16, CUDA), tgt [N] int32, neg [K] or [N,K]
+    int32, mask [N] uint8 (1 = valid).  reduction: "none" (per-position vector, 0 at padded positions), "sum", or
+    "mean" over the valid positions (Eq. 3).  Gradients flow to H and E.
+    """
+    loss = _CceNegLoss.apply(H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps)
+    if reduction == "none":
+        return loss
+    if reduction == "sum":
+        return loss.sum()
+    if reduction == "mean":
+        n_valid = loss.numel() if mask is None else mask.to(torch.float32).sum().clamp_min(1.0)
+        return loss.sum() / n_valid
+    raise ValueError(reduction)
