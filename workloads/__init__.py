@@ -18,4 +18,6 @@ from .generators import (  # noqa: F401
     f32_from_bf16_bits,
     zipf_ids,
     popularity_negatives,
+    popularity_weights,
+    alias_table,
 )

@@ -86,6 +86,41 @@ def popularity_negatives(rng: np.random.Generator, rank_to_id: np.ndarray, K: in
     return rank_to_id[pick].astype(np.int32)
 
 
+def popularity_weights(rank_to_id: np.ndarray, s: float, power: float) -> np.ndarray:
+    """Unnormalised sampling weight per item id: count**power with count ~ rank**(-s) (the law of popularity_negatives)."""
+    V = rank_to_id.shape[0]
+    w = np.empty(V, dtype=np.float64)
+    w[rank_to_id] = np.arange(1, V + 1, dtype=np.float64) ** (-s * power)
+    return w
+
+
+def alias_table(weights: np.ndarray):
+    """Alias table of a discrete law (Walker / Vose): V columns of equal mass 1/V, column c keeps id c with probability
+    thresh[c] / 2^32 and yields alias[c] otherwise.  Returns (thresh uint32 [V], alias int32 [V]).
+
+    Input data for the on-device sampler and for its reference alike: the table is handed to both, neither builds it.
+    """
+    w = np.asarray(weights, dtype=np.float64)
+    V = w.shape[0]
+    q = w * (V / w.sum())                 # mean 1: the share of its own column an id fills
+    alias = np.arange(V, dtype=np.int64)
+    small = [int(x) for x in np.flatnonzero(q < 1.0)]
+    large = [int(x) for x in np.flatnonzero(q >= 1.0)]
+    q = q.copy()
+    while small and large:
+        lo = small.pop()
+        hi = large[-1]
+        alias[lo] = hi                     # the rest of column lo is filled from hi
+        q[hi] -= 1.0 - q[lo]
+        if q[hi] < 1.0:
+            large.pop()
+            small.append(hi)
+    for c in small + large:                # leftovers are full columns up to rounding
+        q[c] = 1.0
+    thresh = np.minimum(np.floor(q * 2.0 ** 32), 2.0 ** 32 - 1).astype(np.uint32)
+    return thresh, alias.astype(np.int32)
+
+
 @dataclass
 class Workload:
     name: str
