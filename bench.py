@@ -124,6 +124,8 @@ def main() -> int:
     ap.add_argument("--filter-eps", type=float, default=0.0, help="gradient filtering threshold (full-catalogue workload c4 only)")
     ap.add_argument("--peaked", action="store_true", help="hidden states that point at their target row: a concentrated softmax, as late in training (c4)")
     ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes the padding compaction of the forward call")
+    ap.add_argument("--sampler", default="none", choices=["none", "uniform", "alias"],
+                    help="draw the negatives inside the kernels (shared / per-position workloads): no index array is read")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run five plain device copies of BYTES (reference for the FETCH_SIZE / WRITE_SIZE counters)")
@@ -177,9 +179,33 @@ def main() -> int:
     dH = torch.empty((w.N, w.d), device="cuda")
     dE = torch.zeros((w.V, w.d), device="cuda")
 
+    smp = None
+    if args.sampler != "none":
+        from hip_harness import device_sampler
+        from workloads import alias_table, popularity_weights
+        table = ()
+        if args.sampler == "alias":   # the popularity law of workload c5 over a seeded rank -> id permutation
+            table = alias_table(popularity_weights(np.random.default_rng(3).permutation(w.V).astype(np.int32), 1.2, 0.75))
+        smp, smp_keep = device_sampler(P.CCE_SAMPLER_UNIFORM if args.sampler == "uniform" else P.CCE_SAMPLER_ALIAS,
+                                       w.notes["seed"], 0, *table)
+        neg = None
+        step_no = [0]
+
+    def forward():
+        if smp is None:
+            return P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        step_no[0] += 1
+        smp.stream = step_no[0] & 0xFFFFFFFF     # other negatives every step; the backward call repeats the number
+        return P.cce_neg_forward_sampled(desc, smp, H, E, tgt, mask, loss, lse, ws)
+
+    def backward():
+        if smp is None:
+            return P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+        return P.cce_neg_backward_sampled(desc_bwd, smp, H, E, tgt, mask, lse, g, dH, dE, ws)
+
     def step():
-        P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
-        P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+        forward()
+        backward()
 
     for _ in range(args.warmup):
         step()
@@ -198,9 +224,9 @@ def main() -> int:
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for k in range(args.steps):
         ev[k][0].record()
-        P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        forward()
         ev[k][1].record()
-        P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+        backward()
         ev[k][2].record()
     torch.cuda.synchronize()
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
@@ -269,7 +295,7 @@ def main() -> int:
         "config": {
             "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
             "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
-            "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": args.filter_eps,
+            "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": args.filter_eps, "sampler": args.sampler,
             "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
             "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
             "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,

@@ -89,8 +89,10 @@ typedef struct {
  *                              results of split launches: 8 bytes per position and forward split, and, for batches
  *                              of at most 40,960 positions, 4 d bytes per position and dH split;
  *   per-position mode:         12 bytes per (position, negative) pair for the inverted index that turns the dE
- *                              scatter into a gather (pairs sorted by item), 4 bytes per table row, 4 per position;
- *   otherwise:                 a 256-byte header.
+ *                              scatter into a gather (pairs sorted by item) and 1/8 byte per pair for the work
+ *                              list of items sampled very often, 4 bytes per table row, 4 per position;
+ *   otherwise:                 a 256-byte header;
+ *   shared mode, in addition:  4 bytes per negative (where the *_sampled calls write the list they draw).
  * No score, probability or gradient-coefficient matrix is ever stored: the workspace holds indices and per-position
  * scalars only.  The same workspace may be reused by later calls on the same stream. */
 size_t cce_neg_workspace_bytes(const cce_desc *desc);
@@ -129,6 +131,49 @@ cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, c
 cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
                             const uint8_t *mask, const float *lse, const float *grad_loss, void *dH, float *dE,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Negative sampling inside the kernels.  The paper draws the negatives of a step on the host (global uniform sampling,
+ * or popularity-based sampling through a multinomial over the catalogue: Sec. 5, "Comparison Sampling Strategies")
+ * and names the stored index matrix as the memory cost of CCE- over CCE (Sec. 5, "What is better").  The *_sampled
+ * calls take a sampler instead of `neg`: every id is a pure function of (seed, stream, position, slot), recomputed
+ * wherever the kernels need it, so the [N,K] matrix is never stored.
+ *   generator  Philox4x32-10 (Salmon et al., SC'11), key = (seed low word, seed high word),
+ *              counter = (q, position low word, position high word, stream)
+ *   slot s (0 <= s < K) of position i is draw j = s + 1
+ *   UNIFORM    q = j >> 2, r = output word j & 3, id = floor(r V / 2^32)
+ *   ALIAS      q = j >> 1, (r0, r1) = output words 2(j & 1), 2(j & 1) + 1, c = floor(r0 V / 2^32),
+ *              id = r1 < alias_thresh[c] ? c : alias_id[c]     (alias method; the caller builds the table for its law)
+ *   CCE_NEG_SHARED uses the draws of position 0 for every position.
+ * Draws are independent (sampling with replacement): repeated ids count once each, an id equal to the position's own
+ * target is handled by mask_target_collisions as for stored negatives.  Change `stream` (or the seed) every step.
+ */
+typedef enum { CCE_SAMPLER_UNIFORM = 1, CCE_SAMPLER_ALIAS = 2 } cce_sampler_kind;
+
+typedef struct {
+    int32_t kind;                 /* cce_sampler_kind */
+    uint32_t stream;              /* fourth counter word: e.g. the training step */
+    uint64_t seed;                /* generator key */
+    const uint32_t *alias_thresh; /* DEVICE [V], ALIAS only: column c keeps id c with probability alias_thresh[c] / 2^32 */
+    const int32_t *alias_id;      /* DEVICE [V], ALIAS only: the id column c yields otherwise; must lie in [0,V) */
+} cce_sampler;
+
+/* Writes the ids the sampler denotes for this descriptor: neg_out [K] (CCE_NEG_SHARED) or [N,K] (CCE_NEG_PER_POSITION,
+ * all positions, padded ones included), DEVICE int32, fully overwritten.  For inspection and tests; the *_sampled
+ * calls do not need it.  CCE_NEG_FULL: CCE_ERR_UNSUPPORTED.  Unknown kind: CCE_ERR_SHAPE.  Missing table: CCE_ERR_NULL. */
+cce_status cce_neg_sample(const cce_desc *desc, const cce_sampler *sampler, int32_t *neg_out, void *hip_stream);
+
+/* cce_neg_forward / cce_neg_backward with neg replaced by the sampler; every other argument, output and error as
+ * there.  Results equal those of the plain calls on the ids cce_neg_sample writes.  Per-position mode: ids of padded
+ * positions are never generated, the forward pass, the backward pass and the index build of the dE pass draw them
+ * again.  Shared mode: the K ids are written to a reserved corner of the workspace first.  Pass the same sampler to
+ * the backward call as to the forward call. */
+cce_status cce_neg_forward_sampled(const cce_desc *desc, const cce_sampler *sampler, const void *H, const void *E,
+                                   const int32_t *tgt, const uint8_t *mask, float *loss, float *lse, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream);
+cce_status cce_neg_backward_sampled(const cce_desc *desc, const cce_sampler *sampler, const void *H, const void *E,
+                                    const int32_t *tgt, const uint8_t *mask, const float *lse, const float *grad_loss,
+                                    void *dH, float *dE, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Synchronises hip_stream and reads the index status word kept in workspace.  Returns CCE_ERR_INDEX if any call on

@@ -20,10 +20,12 @@ CCE_ERR_WORKSPACE, CCE_ERR_UNSUPPORTED, CCE_ERR_HIP = 5, 6, 7
 CCE_F32, CCE_BF16 = 0, 1
 CCE_NEG_SHARED, CCE_NEG_PER_POSITION, CCE_NEG_FULL = 0, 1, 2
 CCE_ALGO_AUTO, CCE_ALGO_GATHER, CCE_ALGO_TILE = 0, 1, 2
+CCE_SAMPLER_UNIFORM, CCE_SAMPLER_ALIAS = 1, 2
 
 EXPORTS = (
     "cce_neg_workspace_bytes", "cce_neg_workspace_init", "cce_neg_forward", "cce_neg_backward",
     "cce_neg_index_status", "cce_status_string", "cce_neg_profile_enable", "cce_neg_profile_read",
+    "cce_neg_sample", "cce_neg_forward_sampled", "cce_neg_backward_sampled",
 )
 
 
@@ -33,6 +35,13 @@ class CceDesc(ctypes.Structure):
         ("in_dtype", ctypes.c_int32), ("dH_dtype", ctypes.c_int32), ("neg_mode", ctypes.c_int32),
         ("mask_target_collisions", ctypes.c_int32), ("validate_indices", ctypes.c_int32), ("algo", ctypes.c_int32),
         ("reuse_forward_prep", ctypes.c_int32), ("filter_eps", ctypes.c_float),
+    ]
+
+
+class CceSampler(ctypes.Structure):
+    _fields_ = [
+        ("kind", ctypes.c_int32), ("stream", ctypes.c_uint32), ("seed", ctypes.c_uint64),
+        ("alias_thresh", ctypes.c_void_p), ("alias_id", ctypes.c_void_p),
     ]
 
 
@@ -62,6 +71,14 @@ def lib() -> ctypes.CDLL:
         L.cce_neg_backward.restype = ctypes.c_int
         L.cce_neg_backward.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
+        L.cce_neg_sample.restype = ctypes.c_int
+        L.cce_neg_sample.argtypes = [ctypes.POINTER(CceDesc), ctypes.POINTER(CceSampler), i32p, vp]
+        L.cce_neg_forward_sampled.restype = ctypes.c_int
+        L.cce_neg_forward_sampled.argtypes = [ctypes.POINTER(CceDesc), ctypes.POINTER(CceSampler), vp, vp, i32p, vp, vp, vp,
+                                              vp, ctypes.c_size_t, vp]
+        L.cce_neg_backward_sampled.restype = ctypes.c_int
+        L.cce_neg_backward_sampled.argtypes = [ctypes.POINTER(CceDesc), ctypes.POINTER(CceSampler), vp, vp, i32p, vp, vp, vp,
+                                               vp, vp, vp, ctypes.c_size_t, vp]
         L.cce_neg_index_status.restype = ctypes.c_int
         L.cce_neg_index_status.argtypes = [vp, ctypes.c_size_t, vp]
         L.cce_neg_profile_enable.restype = ctypes.c_int
@@ -133,6 +150,45 @@ def cce_neg_backward(desc: CceDesc, H, E, tgt, neg, mask, lse, grad_loss, dH, dE
                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     if check and st != CCE_OK:
         raise CceError(st, "cce_neg_backward")
+    return st
+
+
+def make_sampler(kind: int, seed: int, stream: int = 0, alias_thresh: Optional[torch.Tensor] = None,
+                 alias_id: Optional[torch.Tensor] = None) -> CceSampler:
+    """alias_thresh: CUDA tensor of V 32-bit words (the uint32 thresholds, any 4-byte dtype); alias_id: CUDA int32 [V].
+    The sampler only borrows the pointers: keep the tensors alive while it is in use."""
+    s = CceSampler(int(kind), int(stream) & 0xFFFFFFFF, int(seed) & 0xFFFFFFFFFFFFFFFF, None, None)
+    if alias_thresh is not None:
+        s.alias_thresh = _ptr(alias_thresh).value
+    if alias_id is not None:
+        s.alias_id = _ptr(alias_id).value
+    return s
+
+
+def cce_neg_sample(desc: CceDesc, sampler: CceSampler, neg_out, *, check: bool = True) -> int:
+    st = lib().cce_neg_sample(ctypes.byref(desc), ctypes.byref(sampler), _ptr(neg_out), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_sample")
+    return st
+
+
+def cce_neg_forward_sampled(desc: CceDesc, sampler: CceSampler, H, E, tgt, mask, loss, lse, workspace, *,
+                            check: bool = True) -> int:
+    st = lib().cce_neg_forward_sampled(ctypes.byref(desc), ctypes.byref(sampler), _ptr(H), _ptr(E), _ptr(tgt), _ptr(mask),
+                                       _ptr(loss), _ptr(lse), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_forward_sampled")
+    return st
+
+
+def cce_neg_backward_sampled(desc: CceDesc, sampler: CceSampler, H, E, tgt, mask, lse, grad_loss, dH, dE, workspace, *,
+                             check: bool = True) -> int:
+    st = lib().cce_neg_backward_sampled(ctypes.byref(desc), ctypes.byref(sampler), _ptr(H), _ptr(E), _ptr(tgt), _ptr(mask),
+                                        _ptr(lse), _ptr(grad_loss), _ptr(dH), _ptr(dE), _ptr(workspace),
+                                        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_backward_sampled")
     return st
 
 

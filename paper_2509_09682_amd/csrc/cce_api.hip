@@ -136,7 +136,7 @@ Params make_params(const cce_desc *d, const void *H, const void *E, const int32_
 // Workspace of the per-position mode: the correct-item coefficients and the inverted index of the negatives
 // (4 bytes per (position, negative) pair, as large as the `neg` input itself, plus one word per item).
 struct PpLayout {
-    size_t coef, cursor, block_sums, pairs, tmp, part_hist, total;
+    size_t coef, cursor, block_sums, pairs, tmp, part_hist, hot_list, total;
 };
 PpLayout make_pp_layout(const cce_desc *d)
 {
@@ -152,6 +152,7 @@ PpLayout make_pp_layout(const cce_desc *d)
     L.pairs = off;       off += align256(n_pairs * 4);
     L.tmp = off;         off += part ? align256(n_pairs * 8) : 0;
     L.part_hist = off;   off += align256(n_hist * 4);
+    L.hot_list = off;    off += align256(invert_hot_capacity(d->N, d->K) * 16);
     L.total = off;
     return L;
 }
@@ -214,6 +215,38 @@ PrepArgs make_prep_args(const cce_desc *d, const Layout &L, const int32_t *tgt, 
     return p;
 }
 
+// Shared mode: the sampled calls write their K ids behind everything else in the workspace.
+size_t shared_ids_offset(const cce_desc *d)
+{
+    if (use_tile(d)) return make_layout(d).total;
+    if (use_inverted(d)) return make_pp_layout(d).total;
+    return kHeaderBytes;
+}
+
+cce_status check_sampler(const cce_desc *d, const cce_sampler *s)
+{
+    const cce_status st = check_desc(d);
+    if (st != CCE_OK) return st;
+    if (!s) return CCE_ERR_NULL;
+    if (d->neg_mode == CCE_NEG_FULL) return CCE_ERR_UNSUPPORTED;
+    if (s->kind != CCE_SAMPLER_UNIFORM && s->kind != CCE_SAMPLER_ALIAS) return CCE_ERR_SHAPE;
+    if (s->kind == CCE_SAMPLER_ALIAS && (!s->alias_thresh || !s->alias_id)) return CCE_ERR_NULL;
+    return CCE_OK;
+}
+
+Sampler make_sampler(const cce_desc *d, const cce_sampler *s)
+{
+    Sampler r{};
+    r.kind = (uint32_t)s->kind;
+    r.k0 = (uint32_t)(s->seed & 0xffffffffu);
+    r.k1 = (uint32_t)(s->seed >> 32);
+    r.stream = s->stream;
+    r.V = (uint32_t)d->V;
+    r.thresh = s->alias_thresh;
+    r.alias = s->alias_id;
+    return r;
+}
+
 }  // namespace
 
 // ---- profiling records
@@ -268,9 +301,7 @@ extern "C" {
 size_t cce_neg_workspace_bytes(const cce_desc *desc)
 {
     if (cce::check_desc(desc) != CCE_OK) return 0;
-    if (cce::use_tile(desc)) return cce::make_layout(desc).total;
-    if (cce::use_inverted(desc)) return cce::make_pp_layout(desc).total;
-    return cce::kHeaderBytes;
+    return cce::shared_ids_offset(desc) + (desc->neg_mode == CCE_NEG_SHARED ? cce::align256((size_t)desc->K * 4) : 0);
 }
 
 cce_status cce_neg_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -282,14 +313,34 @@ cce_status cce_neg_workspace_init(void *workspace, size_t workspace_bytes, void 
     return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 
-cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
-                           const uint8_t *mask, float *loss, float *lse, void *workspace, size_t workspace_bytes,
-                           void *hip_stream)
+}  // extern "C"
+
+namespace cce {
+namespace {
+
+// Shared mode of the sampled calls: draw the K ids into the workspace and hand them on as a stored list.
+// Per-position mode: the kernels draw; `neg` stays NULL.
+cce_status stage_sampler(const cce_desc *desc, const cce_sampler *sampler, void *workspace, hipStream_t stream,
+                         const int32_t *&neg, Sampler &smp, bool ids_still_there = false)
 {
-    const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
-    if (st != CCE_OK) return st;
-    if (!loss || !lse) return CCE_ERR_NULL;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    smp = Sampler{};
+    neg = nullptr;
+    if (desc->K == 0) return CCE_OK;
+    const Sampler s = make_sampler(desc, sampler);
+    if (desc->neg_mode == CCE_NEG_SHARED) {
+        int32_t *ids = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + shared_ids_offset(desc));
+        if (!ids_still_there && launch_sample(s, 1, desc->K, ids, stream) != hipSuccess) return CCE_ERR_HIP;
+        neg = ids;
+    } else {
+        smp = s;
+    }
+    return CCE_OK;
+}
+
+cce_status forward_impl(const cce_desc *desc, const Sampler &smp, const void *H, const void *E, const int32_t *tgt,
+                        const int32_t *neg, const uint8_t *mask, float *loss, float *lse, void *workspace,
+                        hipStream_t stream)
+{
     if (cce::use_tile(desc)) {
         const cce::Layout L = cce::make_layout(desc);
         cce::PrepArgs pa = cce::make_prep_args(desc, L, tgt, neg, mask, workspace);
@@ -307,18 +358,15 @@ cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, c
     cce::Params p = cce::make_params(desc, H, E, tgt, neg, mask, workspace);
     p.loss = loss;
     p.lse = lse;
+    p.smp = smp;
     const hipError_t e = cce::launch_gather(false, desc->in_dtype == CCE_BF16, p, stream);
     return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
 
-cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
-                            const uint8_t *mask, const float *lse, const float *grad_loss, void *dH, float *dE,
-                            void *workspace, size_t workspace_bytes, void *hip_stream)
+cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H, const void *E, const int32_t *tgt,
+                         const int32_t *neg, const uint8_t *mask, const float *lse, const float *grad_loss, void *dH,
+                         float *dE, void *workspace, hipStream_t stream)
 {
-    const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
-    if (st != CCE_OK) return st;
-    if (!lse || !dH || !dE) return CCE_ERR_NULL;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (cce::use_tile(desc)) {
         const cce::Layout L = cce::make_layout(desc);
         cce::PrepArgs pa = cce::make_prep_args(desc, L, tgt, neg, mask, workspace);
@@ -347,6 +395,7 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     p.g = grad_loss;
     p.dH = dH;
     p.dE = dE;
+    p.smp = smp;
     if (!cce::use_inverted(desc)) {
         const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream);
         return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
@@ -387,13 +436,92 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     ia.pairs = reinterpret_cast<int32_t *>(ws + L.pairs);
     ia.tmp = reinterpret_cast<int2 *>(ws + L.tmp);
     ia.part_hist = reinterpret_cast<int32_t *>(ws + L.part_hist);
+    ia.hot_list = reinterpret_cast<int4 *>(ws + L.hot_list);
+    ia.hot_count = static_cast<int32_t *>(workspace) + cce::kHdrHot;
+    ia.hot_capacity = (int32_t)cce::invert_hot_capacity(desc->N, desc->K);
     ia.N = desc->N;
     ia.V = desc->V;
     ia.d = desc->d;
     ia.K = desc->K;
     ia.collide = desc->mask_target_collisions ? 1 : 0;
     ia.validate = desc->validate_indices ? 1 : 0;
+    ia.smp = smp;
     return cce::launch_inverted_dE(bf16, ia, scatter ? &t : nullptr, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+}
+
+}  // namespace
+}  // namespace cce
+
+extern "C" {
+
+cce_status cce_neg_forward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
+                           const uint8_t *mask, float *loss, float *lse, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
+{
+    const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
+    if (st != CCE_OK) return st;
+    if (!loss || !lse) return CCE_ERR_NULL;
+    return cce::forward_impl(desc, cce::Sampler{}, H, E, tgt, neg, mask, loss, lse, workspace,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
+cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt, const int32_t *neg,
+                            const uint8_t *mask, const float *lse, const float *grad_loss, void *dH, float *dE,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const cce_status st = cce::check_common(desc, H, E, tgt, neg, workspace, workspace_bytes);
+    if (st != CCE_OK) return st;
+    if (!lse || !dH || !dE) return CCE_ERR_NULL;
+    return cce::backward_impl(desc, cce::Sampler{}, H, E, tgt, neg, mask, lse, grad_loss, dH, dE, workspace,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+cce_status cce_neg_sample(const cce_desc *desc, const cce_sampler *sampler, int32_t *neg_out, void *hip_stream)
+{
+    const cce_status st = cce::check_sampler(desc, sampler);
+    if (st != CCE_OK) return st;
+    if (desc->K > 0 && !neg_out) return CCE_ERR_NULL;
+    const int64_t n_pos = (desc->neg_mode == CCE_NEG_SHARED) ? 1 : desc->N;
+    const hipError_t e = cce::launch_sample(cce::make_sampler(desc, sampler), n_pos, desc->K, neg_out,
+                                            static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+}
+
+cce_status cce_neg_forward_sampled(const cce_desc *desc, const cce_sampler *sampler, const void *H, const void *E,
+                                   const int32_t *tgt, const uint8_t *mask, float *loss, float *lse, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    cce_status st = cce::check_sampler(desc, sampler);
+    if (st != CCE_OK) return st;
+    int32_t stand_in = 0;  // the common checks only ask that a list exists when K > 0
+    st = cce::check_common(desc, H, E, tgt, &stand_in, workspace, workspace_bytes);
+    if (st != CCE_OK) return st;
+    if (!loss || !lse) return CCE_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int32_t *neg;
+    cce::Sampler smp;
+    st = cce::stage_sampler(desc, sampler, workspace, stream, neg, smp);
+    if (st != CCE_OK) return st;
+    return cce::forward_impl(desc, smp, H, E, tgt, neg, mask, loss, lse, workspace, stream);
+}
+
+cce_status cce_neg_backward_sampled(const cce_desc *desc, const cce_sampler *sampler, const void *H, const void *E,
+                                    const int32_t *tgt, const uint8_t *mask, const float *lse, const float *grad_loss,
+                                    void *dH, float *dE, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    cce_status st = cce::check_sampler(desc, sampler);
+    if (st != CCE_OK) return st;
+    int32_t stand_in = 0;
+    st = cce::check_common(desc, H, E, tgt, &stand_in, workspace, workspace_bytes);
+    if (st != CCE_OK) return st;
+    if (!lse || !dH || !dE) return CCE_ERR_NULL;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int32_t *neg;
+    cce::Sampler smp;
+    // reuse_forward_prep: the list the forward call drew is still in the workspace
+    st = cce::stage_sampler(desc, sampler, workspace, stream, neg, smp, desc->reuse_forward_prep != 0);
+    if (st != CCE_OK) return st;
+    return cce::backward_impl(desc, smp, H, E, tgt, neg, mask, lse, grad_loss, dH, dE, workspace, stream);
 }
 
 cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream)

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "cce_neg.h"
+#include "cce_sampler.hpp"
 
 namespace cce {
 
@@ -28,6 +29,7 @@ struct Params {
     int32_t skip_neg_dE;    // 1: no dE atomics for negatives
     int32_t skip_pos_dE;    // 1: no dE atomics for the correct item either (the aggregated scatter adds it)
     float *coef;            // [N] out: g_i (p+_i - 1), coefficient of the correct item (nullable)
+    Sampler smp;            // per-position mode, kind != 0: the negatives are drawn in the kernel, neg is not read
 };
 
 constexpr float kLog2e = 1.4426950408889634f;

@@ -10,6 +10,8 @@
 // a wavefront scores 64/LPR candidates per load instruction and UNROLL of those are in flight together.  The dot
 // product is finished with a butterfly over the LPR lanes.  dE updates use a second, interleaved column mapping
 // (lane c owns columns c, c+LPR, ...) so that one atomic instruction covers consecutive addresses of the row.
+#include <type_traits>
+
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
 
@@ -18,6 +20,39 @@ namespace {
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kUnroll = 4;
+constexpr int kWindow = 256;  // per-position negatives: candidate ids a wavefront stages per refill of its LDS window
+
+// Where the ids of the negatives come from.
+enum { IDS_DIRECT = 0,   // shared list (or none): read where needed, every wavefront reads the same cached words
+       IDS_STORED = 1,   // per-position list in memory: staged a window at a time with four coalesced loads
+       IDS_SAMPLED = 2 };  // per-position draws of the counter-based sampler: generated a window at a time
+
+// Per-position negatives: the wavefront fills its LDS window with the ids of candidates [j0, j0 + kWindow) of its
+// position (candidate j >= 1 is slot j - 1 of the list, draw j of the sampler); candidate() reads them from there,
+// so the row gathers never wait for a scattered 4-byte load first.  Sampled: four consecutive draws per lane from one
+// or two generator calls.  LDS operations of one wavefront complete in order, so the reads that follow see the writes.
+template <int IDS>
+__device__ __forceinline__ void refill_window(const Params &p, int64_t i, int64_t j0, int32_t *win)
+{
+    const int lane = threadIdx.x & 63;
+    __builtin_amdgcn_wave_barrier();
+    if (IDS == IDS_SAMPLED) {
+        int32_t id[4];
+        sample4(p.smp, (uint64_t)i, (uint32_t)(j0 >> 2) + lane, id);
+        *reinterpret_cast<int4 *>(win + 4 * lane) = make_int4(id[0], id[1], id[2], id[3]);
+    } else {
+        int32_t id[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int64_t j = j0 + t * 64 + lane;
+            id[t] = (j >= 1 && j <= p.K) ? p.neg[i * (int64_t)p.K + (j - 1)] : 0;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) win[t * 64 + lane] = id[t];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 template <int LPR>
 __device__ __forceinline__ float group_sum(float v)
@@ -34,7 +69,9 @@ struct Cand {
     bool live;
 };
 
-__device__ __forceinline__ Cand candidate(const Params &p, int64_t i, int64_t j, int64_t n_cand, int32_t ti, bool &bad)
+template <int IDS>
+__device__ __forceinline__ Cand candidate(const Params &p, int64_t i, int64_t j, int64_t n_cand, int32_t ti, bool &bad,
+                                          const int32_t *win)
 {
     Cand c{0, false, false};
     if (j >= n_cand) return c;
@@ -50,7 +87,8 @@ __device__ __forceinline__ Cand candidate(const Params &p, int64_t i, int64_t j,
         c.live = true;
         return c;
     }
-    const int32_t id = (p.neg_mode == CCE_NEG_SHARED) ? p.neg[j - 1] : p.neg[i * (int64_t)p.K + (j - 1)];
+    const int32_t id = (IDS != IDS_DIRECT) ? win[j & (kWindow - 1)]
+                                           : ((p.neg_mode == CCE_NEG_SHARED) ? p.neg[j - 1] : p.neg[i * (int64_t)p.K + (j - 1)]);
     c.id = id;
     c.live = !(p.collide && id == ti);
     if (p.validate && (id < 0 || (int64_t)id >= p.V)) {
@@ -60,10 +98,13 @@ __device__ __forceinline__ Cand candidate(const Params &p, int64_t i, int64_t j,
     return c;
 }
 
-template <typename T, int LPR>
+template <typename T, int LPR, int IDS>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params p)
 {
     constexpr int RPI = 64 / LPR;  // candidate rows per wavefront step
+    static_assert(kWindow % (RPI * kUnroll) == 0, "a step never straddles two windows");
+    __shared__ int32_t window[IDS != IDS_DIRECT ? kWavesPerBlock : 1][IDS != IDS_DIRECT ? kWindow : 1];
+    int32_t *win = window[IDS != IDS_DIRECT ? (threadIdx.x >> 6) : 0];
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
     const int grp = lane / LPR;
@@ -98,11 +139,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params 
     float m = -INFINITY, s = 0.f, o_pos = 0.f;
 
     for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
+        if (IDS != IDS_DIRECT && (j0 & (kWindow - 1)) == 0) refill_window<IDS>(p, i, j0, win);
         Cand cd[kUnroll];
         float e[kUnroll][8];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            cd[u] = candidate(p, i, j0 + u * RPI + grp, n_cand, ti, bad);
+            cd[u] = candidate<IDS>(p, i, j0 + u * RPI + grp, n_cand, ti, bad, win);
 #pragma unroll
             for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
             if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
@@ -141,10 +183,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params 
 
 // ATOMIC_DE = false: dE comes from other passes (inverted index, aggregated scatter); this pass yields dH and the
 // correct-item coefficients only.
-template <typename T, int LPR, bool ATOMIC_DE>
+template <typename T, int LPR, bool ATOMIC_DE, int IDS>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params p)
 {
     constexpr int RPI = 64 / LPR;
+    __shared__ int32_t window[IDS != IDS_DIRECT ? kWavesPerBlock : 1][IDS != IDS_DIRECT ? kWindow : 1];
+    int32_t *win = window[IDS != IDS_DIRECT ? (threadIdx.x >> 6) : 0];
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
     const int grp = lane / LPR;
@@ -179,11 +223,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params 
         const int64_t n_cand = (p.neg_mode == CCE_NEG_FULL) ? p.V : (int64_t)p.K + 1;
 
         for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
+            if (IDS != IDS_DIRECT && (j0 & (kWindow - 1)) == 0) refill_window<IDS>(p, i, j0, win);
             Cand cd[kUnroll];
             float e[kUnroll][8];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                cd[u] = candidate(p, i, j0 + u * RPI + grp, n_cand, ti, bad);
+                cd[u] = candidate<IDS>(p, i, j0 + u * RPI + grp, n_cand, ti, bad, win);
 #pragma unroll
                 for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
                 if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
@@ -243,12 +288,19 @@ hipError_t launch_pair(bool backward, const Params &p, hipStream_t stream)
     const dim3 block(kWavesPerBlock * 64);
     const dim3 grid((unsigned)((p.N + kWavesPerBlock - 1) / kWavesPerBlock));
     ProfScope prof(backward ? PROF_GATHER_BWD : PROF_GATHER_FWD, stream);
-    if (backward && p.skip_neg_dE && p.skip_pos_dE)
-        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, false>), grid, block, 0, stream, p);
-    else if (backward)
-        hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, true>), grid, block, 0, stream, p);
-    else
-        hipLaunchKernelGGL((fwd_gather_kernel<T, LPR>), grid, block, 0, stream, p);
+    const int ids = p.smp.kind ? IDS_SAMPLED : ((p.neg_mode == CCE_NEG_PER_POSITION && p.K > 0) ? IDS_STORED : IDS_DIRECT);
+    auto launch = [&](auto tag) {
+        constexpr int IDS = decltype(tag)::value;
+        if (backward && p.skip_neg_dE && p.skip_pos_dE)
+            hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, false, IDS>), grid, block, 0, stream, p);
+        else if (backward)
+            hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, true, IDS>), grid, block, 0, stream, p);
+        else
+            hipLaunchKernelGGL((fwd_gather_kernel<T, LPR, IDS>), grid, block, 0, stream, p);
+    };
+    if (ids == IDS_SAMPLED) launch(std::integral_constant<int, IDS_SAMPLED>{});
+    else if (ids == IDS_STORED) launch(std::integral_constant<int, IDS_STORED>{});
+    else launch(std::integral_constant<int, IDS_DIRECT>{});
     return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ __device__ __forceinline__ bool pair_live(const InvertArgs &a, int64_t pair, int
 {
     const int64_t i = pair / a.K;
     if (a.mask && a.mask[i] == 0) return false;
-    id = a.neg[pair];
+    id = a.smp.kind ? sample1(a.smp, (uint64_t)i, (uint32_t)(pair - i * a.K) + 1u) : a.neg[pair];
     const int32_t ti = a.tgt[i];
     if (a.validate && (ti < 0 || (int64_t)ti >= a.V || id < 0 || (int64_t)id >= a.V)) return false;  // flagged elsewhere
     return !(a.collide && id == ti);
@@ -136,7 +136,7 @@ constexpr int kChunkPairs = 8192;               // pairs per block in level 1
 
 // The pairs of a block's chunk, kPairBatch per thread at a time: all mask bytes are requested first, then ids and
 // targets of the valid positions only (entries of padded positions are never read), so a thread waits for two round
-// trips per batch instead of three per pair.  Fewer than 2^31 pairs on this path: 32-bit pair arithmetic.
+// trips per batch instead of three per pair.  Sampled negatives are drawn again here instead of being read.  Fewer than 2^31 pairs on this path: 32-bit pair arithmetic.
 constexpr int kPairBatch = 8;
 static_assert(kChunkPairs % (kThreads * kPairBatch) == 0, "whole batches per chunk");
 
@@ -158,7 +158,8 @@ __device__ __forceinline__ void for_live_pairs(const InvertArgs &a, int64_t chun
         for (int j = 0; j < kPairBatch; ++j) {
             id[j] = ti[j] = 0;
             if (live[j]) {
-                id[j] = a.neg[p0 + u0 + j * kThreads];
+                const uint32_t pair = p0 + u0 + j * kThreads;
+                id[j] = a.smp.kind ? sample1(a.smp, pos[j], pair - pos[j] * K + 1u) : a.neg[pair];  // slot s is draw s + 1
                 ti[j] = a.tgt[pos[j]];
             }
         }
@@ -240,35 +241,14 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
     }
 }
 
-// One group of LPR lanes per item: e_v stays in registers, the positions that sampled it are walked four at a time.
+// Walks the positions filed in pairs[r, r_end) for the item whose row e the lane group holds, four at a time:
+// recomputes each score against the hidden state (L2-resident), forms g exp(o - lse) and adds G h to acc.
+// Every lane of the wavefront calls it (the loop condition is a wavefront vote, the scalar products use shuffles).
 template <typename T, int LPR>
-__global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
+__device__ __forceinline__ void walk_segment(const InvertArgs &a, const float (&e)[8], int32_t r, int32_t r_end, bool col_ok,
+                                             int c, float (&acc)[8])
 {
-    constexpr int GPW = 64 / LPR;  // items per wavefront
-    const int lane = threadIdx.x & 63;
-    const int c = lane % LPR;
-    const int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * GPW + lane / LPR;
-    const bool col_ok = c * 8 < a.d;
-    int32_t r = 0, r_end = 0;
-    if (v < a.V) {
-        r = (v == 0) ? 0 : a.cursor[v - 1];
-        r_end = a.cursor[v];
-    }
-    if (!__any(r < r_end)) return;
     const T *Hp = static_cast<const T *>(a.H);
-    float e[8], acc[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) e[t] = acc[t] = 0.f;
-    // the item row and the dE row it will be added to are requested together, before the walk over the positions
-    const bool mine = r < r_end && col_ok;
-    float4 *row = reinterpret_cast<float4 *>(a.dE + (mine ? v : 0) * (int64_t)a.d + c * 8);
-    float4 dx = make_float4(0.f, 0.f, 0.f, 0.f), dy = dx;
-    if (mine) {
-        load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
-        dx = row[0];
-        dy = row[1];
-    }
-
     while (__any(r < r_end)) {
         int32_t pos[4];
         float h[4][8], lse[4], g[4];
@@ -301,6 +281,53 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
         }
         r += 4;
     }
+}
+
+// An item sampled by more than kHotPairs positions (popularity-weighted negatives: the head of the law collects
+// percents of all pairs) would keep one lane group walking for milliseconds.  Its segment is cut into chunks of
+// kHotPairs instead, filed in a work list, and hot_item_kernel spreads the chunks over the chip and adds their partial
+// rows with atomics (d atomics per kHotPairs pairs).
+constexpr int kHotPairs = 256;
+
+// One group of LPR lanes per item: e_v stays in registers, the positions that sampled it are walked four at a time.
+template <typename T, int LPR>
+__global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
+{
+    constexpr int GPW = 64 / LPR;  // items per wavefront
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * GPW + lane / LPR;
+    const bool col_ok = c * 8 < a.d;
+    int32_t r = 0, r_end = 0;
+    if (v < a.V) {
+        r = (v == 0) ? 0 : a.cursor[v - 1];
+        r_end = a.cursor[v];
+    }
+    if (!__any(r < r_end)) return;
+    if (r_end - r > kHotPairs) {  // hot item: file its chunks and leave it to hot_item_kernel
+        const int32_t n_chunks = (r_end - r + kHotPairs - 1) / kHotPairs;
+        int32_t slot = 0;
+        if (c == 0) slot = atomicAdd(a.hot_count, n_chunks);
+        slot = __shfl(slot, lane - c, 64);
+        for (int32_t k = c; k < n_chunks; k += LPR) {
+            const int32_t b = r + k * kHotPairs;
+            if (slot + k < a.hot_capacity) a.hot_list[slot + k] = make_int4((int32_t)v, b, min(b + kHotPairs, r_end), 0);
+        }
+        r = r_end = 0;
+    }
+    float e[8], acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) e[t] = acc[t] = 0.f;
+    // the item row and the dE row it will be added to are requested together, before the walk over the positions
+    const bool mine = r < r_end && col_ok;
+    float4 *row = reinterpret_cast<float4 *>(a.dE + (mine ? v : 0) * (int64_t)a.d + c * 8);
+    float4 dx = make_float4(0.f, 0.f, 0.f, 0.f), dy = dx;
+    if (mine) {
+        load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+        dx = row[0];
+        dy = row[1];
+    }
+    walk_segment<T, LPR>(a, e, r, r_end, col_ok, c, acc);
     // the row belongs to this lane group alone: plain read-modify-write
     if (mine) {
         dx.x += acc[0]; dx.y += acc[1]; dx.z += acc[2]; dx.w += acc[3];
@@ -310,13 +337,50 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
     }
 }
 
+// The chunks item_dE_kernel filed: one lane group per chunk, a fixed grid strides over the list.
+constexpr int kHotBlocks = 1024;
+template <typename T, int LPR>
+__global__ __launch_bounds__(kThreads) void hot_item_kernel(InvertArgs a)
+{
+    constexpr int GPW = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const bool col_ok = c * 8 < a.d;
+    const int32_t n = min(*a.hot_count, a.hot_capacity);
+    const int32_t stride = (int32_t)gridDim.x * (kThreads / 64) * GPW;
+    for (int32_t e0 = ((int32_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * GPW; e0 < n; e0 += stride) {
+        const int32_t ent = e0 + lane / LPR;  // e0 is the same for the whole wavefront
+        int32_t v = 0, r = 0, r_end = 0;
+        if (ent < n) {
+            const int4 t = a.hot_list[ent];
+            v = t.x;
+            r = t.y;
+            r_end = t.z;
+        }
+        float e[8], acc[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) e[t] = acc[t] = 0.f;
+        const bool mine = r < r_end && col_ok;
+        if (mine) load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+        walk_segment<T, LPR>(a, e, r, r_end, col_ok, c, acc);
+        if (mine) {
+            float *row = a.dE + v * (int64_t)a.d + c * 8;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) unsafeAtomicAdd(row + t, acc[t]);
+        }
+    }
+}
+
 template <typename T, int LPR>
 hipError_t launch_item_dE(const InvertArgs &a, hipStream_t stream)
 {
     constexpr int items_per_block = (kThreads / 64) * (64 / LPR);
     ProfScope prof(PROF_ITEM_DE, stream);
+    hipError_t e = launch_fill_zero(a.hot_count, 1, stream);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((item_dE_kernel<T, LPR>), dim3((unsigned)((a.V + items_per_block - 1) / items_per_block)),
                        dim3(kThreads), 0, stream, a);
+    hipLaunchKernelGGL((hot_item_kernel<T, LPR>), dim3(kHotBlocks), dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -332,8 +396,34 @@ hipError_t launch_item_dE_by_width(const InvertArgs &a, hipStream_t stream)
     return launch_item_dE<T, 64>(a, stream);
 }
 
+// One thread per four consecutive draws of a position.
+__global__ __launch_bounds__(kThreads) void sample_kernel(Sampler smp, int64_t n_pos, int32_t K, int32_t *out)
+{
+    const int64_t quads = ((int64_t)K + 4) / 4;  // draws 0..K cover K/4 + 1 groups of four
+    const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (t >= n_pos * quads) return;
+    const int64_t i = t / quads;
+    const uint32_t q4 = (uint32_t)(t - i * quads);
+    int32_t id[4];
+    sample4(smp, (uint64_t)i, q4, id);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int64_t j = 4 * (int64_t)q4 + w;  // draw number; slot j - 1
+        if (j >= 1 && j <= K) out[i * K + (j - 1)] = id[w];
+    }
+}
+
 }  // namespace
 
+hipError_t launch_sample(const Sampler &smp, int64_t n_pos, int32_t K, int32_t *out, hipStream_t stream)
+{
+    const int64_t threads = n_pos * (((int64_t)K + 4) / 4);
+    if (n_pos <= 0 || K <= 0) return hipSuccess;
+    hipLaunchKernelGGL(sample_kernel, dim3((unsigned)((threads + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream, smp, n_pos, K, out);
+    return hipGetLastError();
+}
+
+size_t invert_hot_capacity(int64_t N, int64_t K) { return (size_t)(2 * (N * K / kHotPairs) + 16); }
 size_t invert_scan_blocks(int64_t n) { return (size_t)((n + kScanChunk - 1) / kScanChunk); }
 int64_t invert_part_blocks(int64_t N, int64_t K) { return (N * K + kChunkPairs - 1) / kChunkPairs; }
 int64_t invert_buckets(int64_t V) { return (V + kBucketIds - 1) / kBucketIds; }

@@ -7,7 +7,7 @@
 namespace cce {
 
 // 32-bit words of the workspace header.
-enum { kHdrStatus = 0, kHdrTotal = 1, kHdrDone = 2, kHdrNValid = 3 };
+enum { kHdrStatus = 0, kHdrTotal = 1, kHdrDone = 2, kHdrNValid = 3, kHdrHot = 4 };
 
 // ---- row-gather family: one wavefront per position; any mode, fp32 or bf16 inputs
 hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream);
@@ -73,9 +73,14 @@ struct InvertArgs {
     int2 *tmp;               // [N*K] workspace: (id, position) partitioned by bucket
     int32_t *part_hist;      // [n_buckets * n_part_blocks + 1] workspace: (bucket, block) counts -> offsets
     int32_t *part_total;     // = part_hist + n_buckets * n_part_blocks (set by the launcher)
+    int4 *hot_list;          // [hot_capacity] workspace: (item, first pair, end pair, -) chunks of items with long segments
+    int32_t *hot_count;      // workspace header word: chunks filed
+    int32_t hot_capacity;
     int64_t N, V, n_part_blocks;
     int32_t d, K, collide, validate, n_buckets;
+    Sampler smp;             // kind != 0: the negatives are drawn again here instead of being read from neg
 };
+size_t invert_hot_capacity(int64_t N, int64_t K);  // entries of hot_list
 size_t invert_scan_blocks(int64_t n);          // blocks of the scan over n words (size of block_sums)
 int64_t invert_part_blocks(int64_t N, int64_t K);
 int64_t invert_buckets(int64_t V);
@@ -99,6 +104,9 @@ struct ProfScope {
     int slot;
     hipStream_t stream;
 };
+
+// Writes the ids a sampler denotes: out[n_pos, K], row i = draws 1..K of position i (n_pos = 1: the shared list).
+hipError_t launch_sample(const Sampler &smp, int64_t n_pos, int32_t K, int32_t *out, hipStream_t stream);
 
 // Clears `words` 32-bit words at dst with a fill kernel (no memset node).
 hipError_t launch_fill_zero(int32_t *dst, size_t words, hipStream_t stream);

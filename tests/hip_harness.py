@@ -56,3 +56,43 @@ def run_hip(w, *, g: Optional[np.ndarray] = "workload", algo=P.CCE_ALGO_AUTO, dH
     torch.cuda.synchronize()
     return dict(loss=loss.cpu().numpy(), lse=lse.cpu().numpy(), dH=dH.float().cpu().numpy(), dE=dE.cpu().numpy(),
                 status=status)
+
+
+def device_sampler(kind, seed, stream, thresh=None, alias=None):
+    """Sampler descriptor plus the device tensors it borrows (keep the tuple alive while the sampler is used)."""
+    keep = []
+    th = al = None
+    if thresh is not None:
+        th = torch.from_numpy(thresh.view(np.int32)).to("cuda")   # same 32-bit words
+        al = torch.from_numpy(alias).to("cuda")
+        keep = [th, al]
+    return P.make_sampler(kind, seed, stream, th, al), keep
+
+
+def sample_hip(w, smp):
+    """The ids the library's sampler denotes for the workload's shape: numpy int32 [K] or [N,K]."""
+    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode)
+    shape = (w.K,) if w.neg_mode == P.CCE_NEG_SHARED else (w.N, w.K)
+    out = torch.full(shape, -7, dtype=torch.int32, device="cuda")
+    P.cce_neg_sample(desc, smp, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def run_hip_sampled(w, smp, *, algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32):
+    """Forward + backward through the *_sampled calls (w.neg is ignored).  Same result dict as run_hip."""
+    H, E, tgt, _, mask = to_device(w)
+    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
+                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, algo=algo)
+    ws = P.new_workspace(desc)
+    loss = torch.full((w.N,), float("nan"), device="cuda")
+    lse = torch.full((w.N,), float("nan"), device="cuda")
+    P.cce_neg_forward_sampled(desc, smp, H, E, tgt, mask, loss, lse, ws)
+    g_t = torch.from_numpy(w.g).to("cuda")
+    dH = torch.full((w.N, w.d), float("nan"), device="cuda", dtype=torch.bfloat16 if dH_dtype == P.CCE_BF16 else torch.float32)
+    dE = torch.zeros((w.V, w.d), device="cuda")
+    P.cce_neg_backward_sampled(desc, smp, H, E, tgt, mask, lse, g_t, dH, dE, ws)
+    status = P.cce_neg_index_status(ws)
+    torch.cuda.synchronize()
+    return dict(loss=loss.cpu().numpy(), lse=lse.cpu().numpy(), dH=dH.float().cpu().numpy(), dE=dE.cpu().numpy(),
+                status=status)

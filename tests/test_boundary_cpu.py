@@ -93,3 +93,35 @@ def test_gradient_filtering_is_accepted_only_where_it_is_defined(binding):
         assert B.cce_neg_workspace_bytes(desc) == 0
     for bad in (-1.0, float("nan")):
         assert B.cce_neg_workspace_bytes(B.make_desc(256, 1000, 64, 0, B.CCE_BF16, B.CCE_NEG_FULL, filter_eps=bad)) == 0
+
+
+def test_sampled_calls_reject_bad_samplers_before_launch(binding):
+    B = binding
+    L = B.lib()
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced
+    desc = B.make_desc(16, 100, 64, 8, B.CCE_F32, B.CCE_NEG_PER_POSITION)
+    ok = B.make_sampler(B.CCE_SAMPLER_UNIFORM, 1, 0)
+    assert L.cce_neg_sample(ctypes.byref(desc), None, fake, None) == B.CCE_ERR_NULL
+    assert L.cce_neg_sample(ctypes.byref(desc), ctypes.byref(ok), None, None) == B.CCE_ERR_NULL
+    assert L.cce_neg_sample(ctypes.byref(desc), ctypes.byref(B.make_sampler(7, 1, 0)), fake, None) == B.CCE_ERR_SHAPE
+    alias_without_table = B.make_sampler(B.CCE_SAMPLER_ALIAS, 1, 0)
+    assert L.cce_neg_sample(ctypes.byref(desc), ctypes.byref(alias_without_table), fake, None) == B.CCE_ERR_NULL
+    full = B.make_desc(16, 100, 64, 0, B.CCE_F32, B.CCE_NEG_FULL)
+    assert L.cce_neg_sample(ctypes.byref(full), ctypes.byref(ok), fake, None) == B.CCE_ERR_UNSUPPORTED
+    big = 1 << 30
+    st = L.cce_neg_forward_sampled(ctypes.byref(full), ctypes.byref(ok), fake, fake, fake, None, fake, fake, fake, big, None)
+    assert st == B.CCE_ERR_UNSUPPORTED
+    st = L.cce_neg_forward_sampled(ctypes.byref(desc), ctypes.byref(ok), fake, fake, None, None, fake, fake, fake, big, None)
+    assert st == B.CCE_ERR_NULL   # tgt missing
+    st = L.cce_neg_forward_sampled(ctypes.byref(desc), ctypes.byref(ok), fake, fake, fake, None, fake, fake, fake, 8, None)
+    assert st == B.CCE_ERR_WORKSPACE
+    st = L.cce_neg_backward_sampled(ctypes.byref(desc), ctypes.byref(ok), fake, fake, fake, None, None, None, fake, fake,
+                                    fake, big, None)
+    assert st == B.CCE_ERR_NULL   # lse missing
+    st = L.cce_neg_backward_sampled(ctypes.byref(desc), ctypes.byref(alias_without_table), fake, fake, fake, None, fake,
+                                    None, fake, fake, fake, big, None)
+    assert st == B.CCE_ERR_NULL
+    # the shared list the sampled calls draw has its corner of the workspace
+    a = B.cce_neg_workspace_bytes(B.make_desc(512, 4096, 64, 128, B.CCE_F32, B.CCE_NEG_SHARED))
+    b = B.cce_neg_workspace_bytes(B.make_desc(512, 4096, 64, 1024, B.CCE_F32, B.CCE_NEG_SHARED))
+    assert b - a >= (1024 - 128) * 4

@@ -385,3 +385,22 @@ def test_full_size_large_configs_on_sampled_positions(idx, n_sample):
         assert np.all(np.isin(changed, touched))
         # every row of a target or negative normally receives a non-zero gradient; allow exact cancellations
         assert changed.size >= 0.999 * touched.size
+
+
+@pytest.mark.parametrize("case", ["all_hot", "zipf_head"])
+def test_per_position_negatives_with_items_sampled_very_often(case):
+    """Items with more pairs than one lane group walks are cut into chunks and added by the work-list kernel."""
+    import dataclasses
+
+    from workloads import zipf_ids
+
+    if case == "all_hot":      # 50 items, 600 x 64 pairs: every item has several hundred pairs
+        w = make_workload("hot", 600, 1, 128, 50, 64, "bf16", NEG_PER_POSITION, 31, g_kind="random", pad="bernoulli", pad_p=0.1)
+    else:                      # power-law negatives: the head is hot, the tail is sampled once or never
+        w = make_workload("hot", 900, 1, 64, 3000, 128, "bf16", NEG_PER_POSITION, 32, g_kind="random")
+        rng = np.random.default_rng(5)
+        ids, _ = zipf_ids(rng, rng, w.N * w.K, w.V, 1.3)
+        w = dataclasses.replace(w, neg=ids.reshape(w.N, w.K))
+    counts = np.bincount(w.neg[w.mask != 0].ravel(), minlength=w.V)
+    assert counts.max() > 600 and (case == "all_hot" or (counts <= 4).sum() > 100)   # one lane group walks 256 pairs
+    check_against_oracle(w, _run(w), 2e-5)
