@@ -383,6 +383,9 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
         a.dE = dE;
         a.write_consts = 1;
         a.filter_log2 = desc->filter_eps > 0.f ? log2f(desc->filter_eps) : -INFINITY;
+        // The forward call leaves the per-position constants of the backward pass that do not involve the upstream
+        // gradient; a caller who vouches for the workspace spares the pass that would recompute them.
+        a.g_separate = (desc->reuse_forward_prep && grad_loss && cce::tile_backward_fusable(desc->d)) ? 1 : 0;
         cce::TileArgs a_de = a;
         a_de.splits = L.splits_de;
         if (cce::tile_backward_fusable(desc->d))  // both passes in one launch, behind a small per-position pass

@@ -50,6 +50,8 @@ struct TileArgs {
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
     int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
     float filter_log2;           // backward, gradient filtering: log2 of the threshold; -inf = off
+    int32_t g_separate;          // backward: coef and de_const[0] are what the FORWARD pass left (no upstream gradient in
+                                 // them): the scatter multiplies by g itself and the dE pass streams g by row number
 };
 
 enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items

@@ -181,7 +181,9 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                                           uint16_t *const buf2, uint16_t *const buf3, float *const epi_own)
 {
     constexpr bool BWD_MODE = (MODE != MODE_FWD);
-    constexpr bool SWP = (BY % 64 == 0) && (D <= 128);  // the pipelined sub-tile loop alternates between two register sets
+    // The pipelined sub-tile loop alternates between two register sets; above d = 128 only the forward pass with one
+    // group of stationary rows has the registers for it (the operands of a whole sub-tile are d/4 registers).
+    constexpr bool SWP = (BY % 64 == 0) && (D <= 128 || (MODE == MODE_FWD && XG == 1));
     constexpr int KK = D / 16;             // k-steps of the score product
     constexpr int MB = D / 32;             // 32-row output blocks of the second product
     constexpr int CPR = D / 8;             // 16-byte chunks per row
@@ -326,7 +328,17 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     };
     // Row numbers of a tile's rows, as each lane needs them for its LPW load instructions: straight from global memory
     // (prologue), or from the copy that an earlier load group left in LDS.
-    auto rows_from_global = [&](int64_t t, int32_t (&rows)[LPW]) {
+    // rows[LPW] is the row whose constant (dE pass) this lane's constant load fetches.
+    constexpr int NR = LPW + 1;
+    constexpr bool GSEP = (MODE == MODE_DE) && D <= 128;  // only the fused backward launch (hidden sizes up to 128) uses it
+    auto const_row_slot = [&]() -> int { return ((wave % CI) * 64 + lane) % BY; };
+    auto rows_from_global = [&](int64_t t, int32_t (&rows)[NR]) {
+        rows[LPW] = 0;
+        if (GSEP && a.g_separate) {
+            int64_t y = t * BY + const_row_slot();
+            if (y >= n_y) y = n_y - 1;
+            rows[LPW] = ind ? ind[y] : (int32_t)y;
+        }
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int r = ((wave + i * NW) * 64 + lane) / CPR;
@@ -335,8 +347,13 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             rows[i] = ind ? checked_row(ind[y]) : (int32_t)y;
         }
     };
-    auto rows_from_lds = [&](int64_t t, const uint16_t *holder, int32_t (&rows)[LPW]) {
+    auto rows_from_lds = [&](int64_t t, const uint16_t *holder, int32_t (&rows)[NR]) {
         const int32_t *ids = reinterpret_cast<const int32_t *>(holder + OFF_I);
+        rows[LPW] = 0;
+        if (GSEP && a.g_separate) {
+            const int64_t y = t * BY + const_row_slot();
+            rows[LPW] = ind ? ids[const_row_slot()] : (int32_t)(y < n_y ? y : n_y - 1);
+        }
         if (ind) {
 #pragma unroll
             for (int i = 0; i < LPW; ++i) rows[i] = checked_row(ids[((wave + i * NW) * 64 + lane) / CPR]);
@@ -362,7 +379,16 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     const bool small_table = (uint64_t)((MODE == MODE_DE) ? a.N : a.V) * (uint64_t)(D * 2) <= 0xffffffffull;
     const char *const Ybytes = reinterpret_cast<const char *>(Ybase);
     const uint32_t last_y = (uint32_t)(n_y - 1);
-    auto issue_group = [&](int64_t t, const int32_t (&rows)[LPW], uint16_t *dst) {
+    // The destination reaches the load instructions as a bare LDS offset that the optimiser cannot trace back to its
+    // array.  Otherwise the compiler, which does not see the counted waits of the ring (they are inline assembly),
+    // protects the one buffer that is filled and read within one trip of the unrolled loop with a wait for ALL loads in
+    // flight, placed right after the group of the next tile has been issued: the load latency of every NBUF-th tile
+    // was then exposed in full.  That a tile has landed before it is read is the business of wait_for_next() and the
+    // barrier behind it, for every buffer alike.
+    auto issue_group = [&](int64_t t, const int32_t (&rows)[NR], uint16_t *dst_generic) {
+        uint32_t dst_lds = (uint32_t)(uintptr_t)(lds_ptr)dst_generic;
+        asm volatile("" : "+s"(dst_lds));
+        uint16_t __attribute__((address_space(3))) *dst = (uint16_t __attribute__((address_space(3))) *)(uintptr_t)dst_lds;
         if (small_table) {
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
@@ -382,6 +408,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             uint32_t y = (uint32_t)(t * BY) + (uint32_t)(e % BY);  // t * BY < n_y < 2^31
             if (y > last_y) y = last_y;
             const uint32_t *src = a.de_const + (int64_t)(e / BY) * a.N + y;
+            // upstream gradient straight from the caller's array, by row number, where the forward pass left the rest
+            if (GSEP && a.g_separate && e / BY == 1) src = reinterpret_cast<const uint32_t *>(a.g) + rows[LPW];
             __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + OFF_C + inst * 128), 4, 0, 0);
         }
         if (ind) {
@@ -604,7 +632,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             bool kept[2] = {true, true};  // gradient filtering: whether the sub-tile of either register set survived
             // Forward: operands two sub-tiles ahead (nothing else covers their latency).  Backward: one ahead, and the
             // second product of the previous sub-tile goes to the matrix pipe before the score product that needs them.
-            constexpr int OPD = BWD ? 1 : 2;
+            constexpr int OPD = (BWD || D > 128) ? 1 : 2;
             load_ops(tile, 0, op[0]);
             if (OPD == 2 && NSB > 1) load_ops(tile, 1, op[1]);
             mfma_scores(op[0], sv[0]);
@@ -650,8 +678,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 __builtin_amdgcn_sched_group_barrier(0x008, NM_P, 0);
             }
         } else {
-            // Large hidden sizes: no room for a second sub-tile in flight, the other wavefront of the SIMD fills the
-            // gaps.  What must not happen is one LDS read per matrix instruction with the read issued just ahead of
+            // Large hidden sizes, backward passes: no room for a second sub-tile in flight, the other wavefront of the
+            // SIMD fills the gaps.  What must not happen is one LDS read per matrix instruction with the read issued just ahead of
             // it, as the compiler orders them: LDS latency is several times the 32 cycles of a matrix instruction.
             // Operands are therefore read in batches of four into two alternating register sets, and every batch is
             // requested one batch of matrix instructions ahead of its use.
@@ -762,7 +790,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     };
     auto step = [&](int64_t t, const uint16_t *cur, uint16_t *nxt) {
         if (t + PF < t_end) {
-            int32_t rows[LPW];
+            int32_t rows[NR];
             rows_from_lds(t + PF, cur, rows);
             issue_group(t + PF, rows, nxt);
         }
@@ -772,7 +800,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         barrier_keep_loads();
     };
     if (t_begin < t_end) {
-        int32_t rows[PF][LPW];
+        int32_t rows[PF][NR];
 #pragma unroll
         for (int j = 0; j < PF; ++j)
             if (t_begin + j < t_end) rows_from_global(t_begin + j, rows[j]);
@@ -850,6 +878,11 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 const float l = (M + __builtin_amdgcn_logf(tot)) * kLn2;
                 a.lse[xrow[g]] = l;
                 a.loss[xrow[g]] = l - op;
+                // what a backward call that reuses this call's preparation needs per position, short of the upstream
+                // gradient: the correct item's coefficient w p+ - 1 and the exponent offset of the dE pass
+                const float nl = -l * kLog2e;
+                a.coef[xrow[g]] = w * __builtin_amdgcn_exp2f(fmaf(op, kLog2e, nl)) - 1.f;
+                a.de_const[x] = __float_as_uint(nl);
             }
         }
     } else if (MODE == MODE_DH) {
@@ -1181,6 +1214,9 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(TileArgs a)
         const float l = (M + __builtin_amdgcn_logf(tot)) * kLn2;
         a.lse[row] = l;
         a.loss[row] = l - op;
+        const float nl = -l * kLog2e;  // as in the unsplit epilogue
+        a.coef[row] = w * __builtin_amdgcn_exp2f(fmaf(op, kLog2e, nl)) - 1.f;
+        a.de_const[x] = __float_as_uint(nl);
     }
 }
 
@@ -1324,6 +1360,9 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     // Forward: 16 KiB of bf16 per tile buffer (128 rows at d = 64, 32 rows at d = 256); three blocks per compute unit
     // at d = 64 (register budget 168), else two.
     constexpr int BY = 8192 / D;
+    // d = 256, forward: tiles of four sub-tiles, so that the software-pipelined loop (score product of sub-tile k + 1
+    // under the softmax arithmetic of sub-tile k) has something to overlap in three phases out of four.
+    constexpr int BY_F = (D <= 128) ? BY : 128;
     constexpr int MINB_F = (D <= 64) ? 3 : 2;
     // d = 256: every block streams the whole other operand from L2 (about 12 TB/s over the chip for direct-to-LDS
     // loads), so the rows it keeps stationary decide the traffic: eight wavefronts per block, one block per compute
@@ -1334,9 +1373,10 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     constexpr int BY_B = BY;
     constexpr int MINB = (D <= 128) ? 2 : 1;   // backward: 256 registers per wavefront
     // LDS buffers in flight, 18 KiB each: three blocks per compute unit leave room for three of them, two blocks or
-    // one for four.
+    // one for four.  d = 256: two 66-KiB buffers in the forward pass; three buffers in the backward passes (measured:
+    // dE 5 % faster than with two, dH unchanged, four no better).
     constexpr int NBUF_F = (D <= 64) ? 3 : (D <= 128 ? 4 : 2);
-    constexpr int NBUF_B = (D <= 128) ? 4 : 2;
+    constexpr int NBUF_B = (D <= 128) ? 4 : 3;
     // Two groups of stationary rows per wavefront use each LDS operand for two matrix instructions; the backward
     // accumulators leave room for that up to d = 64.
     constexpr int XG_F = 2;
@@ -1351,10 +1391,12 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     };
     switch (pass) {
     case TILE_PASS_FWD:
-        if (wide(a.N, true))
-            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, XG_F, (D <= 128 ? 2 : 1), (D <= 128 ? 4 : 2)>(a, a.N, stream);
+        if constexpr (D > 128) {  // one group of stationary rows per wavefront: registers for two score tiles in flight
+            e = launch_tile_kernel<D, MODE_FWD, BY_F, NW_L, 1, 1, NBUF_F>(a, a.N, stream);
+        } else if (wide(a.N, true))
+            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, XG_F, 2, 4>(a, a.N, stream);
         else
-            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, 1, (D <= 128 ? MINB_F : 1), NBUF_F>(a, a.N, stream);
+            e = launch_tile_kernel<D, MODE_FWD, BY, NW_L, 1, MINB_F, NBUF_F>(a, a.N, stream);
         if (e == hipSuccess && a.splits > 1) {
             ProfScope prof(PROF_FWD_MERGE, stream);
             hipLaunchKernelGGL((fwd_merge_kernel<D>), dim3((unsigned)((a.N * 8 + 255) / 256)), dim3(256), 0, stream, a);
@@ -1400,7 +1442,7 @@ hipError_t launch_bwd_for_d(TileArgs a_dh, TileArgs a_de, hipStream_t stream)
 {
     constexpr int XG_B = (D <= 64) ? 2 : 1;
     a_dh.write_consts = 0;
-    {
+    if (!a_dh.g_separate) {
         constexpr int PPB = 256 / (D / 8);
         ProfScope prof(PROF_BWD_PRE, stream);
         hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)((a_dh.N + PPB - 1) / PPB)), dim3(256), 0, stream, a_dh);
