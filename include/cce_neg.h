@@ -72,9 +72,12 @@ typedef struct {
     int32_t algo;                   /* cce_algo */
     int32_t reuse_forward_prep;     /* backward only, 1: the caller vouches that the workspace still holds what the
                                        forward call with this descriptor and the same tgt / neg / mask contents left
-                                       there (nothing else wrote to it since), so the compaction of padded positions
-                                       and the collision counts are not recomputed.  0: no assumption.  With 1 and a
-                                       workspace that does not hold them the results are undefined. */
+                                       there (nothing else wrote to it since), so the compaction of padded positions,
+                                       the collision counts and (hidden sizes up to 128, grad_loss given) the
+                                       per-position constants that the forward call files for the backward pass are
+                                       not recomputed; lse must then be the forward call's own output.  0: no
+                                       assumption.  With 1 and a workspace that does not hold them the results are
+                                       undefined. */
     float filter_eps;               /* backward only, gradient filtering of the full-catalogue mode (Sec. 3.1, last
                                        paragraph; Sec. 4.3): 0 = off.  > 0: the softmax matrix of the valid positions
                                        (batch order) by the items (id order) is cut into 32 x 32 blocks aligned at the

@@ -29,12 +29,15 @@ def _workspace(desc: B.CceDesc, device):
 
 class _CceNegLoss(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps):
+    def forward(ctx, H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps, sampler, n_neg):
         if H.dtype != E.dtype or H.dtype not in (torch.float32, torch.bfloat16):
             raise TypeError("H and E must both be float32 or both be bfloat16")
         N, d = H.shape
         V = E.shape[0]
-        K = 0 if neg is None or neg_mode == B.CCE_NEG_FULL else int(neg.shape[-1])
+        if sampler is not None:
+            K = int(n_neg)
+        else:
+            K = 0 if neg is None or neg_mode == B.CCE_NEG_FULL else int(neg.shape[-1])
         dt = B.CCE_F32 if H.dtype == torch.float32 else B.CCE_BF16
         kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0)
         desc = B.make_desc(N, V, d, K, dt, neg_mode, **kw)
@@ -46,7 +49,11 @@ class _CceNegLoss(torch.autograd.Function):
         H, E = H.contiguous(), E.contiguous()
         loss = torch.empty(N, device=H.device, dtype=torch.float32)
         lse = torch.empty(N, device=H.device, dtype=torch.float32)
-        B.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        if sampler is not None:
+            B.cce_neg_forward_sampled(desc, sampler, H, E, tgt, mask, loss, lse, ws)
+        else:
+            B.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        ctx.sampler = sampler   # the backward call draws the same ids again
         ctx.save_for_backward(H, E, tgt, neg, mask, lse)
         ctx.bwd = (N, V, d, K, dt, neg_mode, filter_eps, kw)
         ctx.ws = ws
@@ -63,20 +70,29 @@ class _CceNegLoss(torch.autograd.Function):
         # shape has overwritten it since (two loss terms in one graph)
         reuse = 1 if _last_forward.get(ctx.key) == ctx.serial else 0
         desc = B.make_desc(N, V, d, K, dt, neg_mode, reuse_forward_prep=reuse, filter_eps=filter_eps, **kw)
-        B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE, ctx.ws)
-        return dH, dE.to(E.dtype), None, None, None, None, None, None
+        if ctx.sampler is not None:
+            B.cce_neg_backward_sampled(desc, ctx.sampler, H, E, tgt, mask, lse, g, dH, dE, ctx.ws)
+        else:
+            B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE, ctx.ws)
+        return dH, dE.to(E.dtype), None, None, None, None, None, None, None, None
 
 
 def cce_neg_loss(H: torch.Tensor, E: torch.Tensor, tgt: torch.Tensor, neg: Optional[torch.Tensor] = None,
                  mask: Optional[torch.Tensor] = None, *, neg_mode: int = B.CCE_NEG_SHARED, reduction: str = "mean",
-                 mask_target_collisions: bool = True, filter_eps: float = 0.0) -> torch.Tensor:
+                 mask_target_collisions: bool = True, filter_eps: float = 0.0, sampler: Optional[B.CceSampler] = None,
+                 n_neg: int = 0) -> torch.Tensor:
     """Cross-entropy with negative sampling (Eq. 3-5), or over the full catalogue with neg_mode = CCE_NEG_FULL (Eq. 1-2).
 
     H [N,d] hidden states, E [V,d] item table (both float32 or both bfloat16, CUDA), tgt [N] int32, neg [K] or [N,K]
     int32, mask [N] uint8 (1 = valid).  reduction: "none" (per-position vector, 0 at padded positions), "sum", or
     "mean" over the valid positions (Eq. 3).  Gradients flow to H and E.
+
+    sampler (binding.make_sampler) with n_neg = K instead of neg: the negatives are drawn inside the kernels, in the
+    forward and again in the backward pass, and no index tensor exists; give the sampler another `stream` every step.
     """
-    loss = _CceNegLoss.apply(H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps)
+    if sampler is not None:
+        sampler = B.CceSampler(sampler.kind, sampler.stream, sampler.seed, sampler.alias_thresh, sampler.alias_id)  # frozen copy
+    loss = _CceNegLoss.apply(H, E, tgt, neg, mask, neg_mode, mask_target_collisions, filter_eps, sampler, n_neg)
     if reduction == "none":
         return loss
     if reduction == "sum":

@@ -41,7 +41,7 @@ def test_mean_loss_and_its_gradients(idx, scale, tol):
     ref = O.run_workload(w, g=w.g.astype(np.float64))
     valid = w.mask != 0
     ref_mean = float(ref.loss[valid].mean())
-    assert abs(float(loss) - ref_mean) <= tol * max(abs(ref_mean), float(np.abs(ref.lse[valid]).mean()))
+    assert abs(float(loss.detach()) - ref_mean) <= tol * max(abs(ref_mean), float(np.abs(ref.lse[valid]).mean()))
     assert H.grad.dtype == H.dtype and E.grad.dtype == E.dtype
     e_dH = tensor_rel(H.grad.float().cpu().numpy(), ref.dH)
     e_dE = tensor_rel(E.grad.float().cpu().numpy(), ref.dE)
@@ -88,3 +88,25 @@ def test_reductions_agree():
     assert float(vec[mask == 0].abs().max()) == 0.0
     assert abs(float(vec.sum()) - float(total)) <= 1e-6 * abs(float(total))
     assert abs(float(total) / n_valid - float(mean)) <= 1e-6 * abs(float(mean))
+
+
+@pytest.mark.parametrize("idx,scale,tol", [(2, 0.03, 2e-2), (3, 0.02, 2e-2)])
+def test_loss_with_negatives_sampled_in_the_kernels(idx, scale, tol):
+    """cce_neg_loss with a sampler against the oracle run on the reference sampler's ids; the sampler object may be
+    changed by the caller between forward and backward (the loss keeps its own copy)."""
+    import paper_2509_09682_amd as P
+    from oracle import sampler as S
+
+    w = config(idx, scale=scale, g_kind="mean")
+    H, E, tgt, _, mask = _leaves(w)
+    smp = P.make_sampler(P.CCE_SAMPLER_UNIFORM, 31337, 4)
+    loss = P.cce_neg_loss(H, E, tgt, None, mask, neg_mode=w.neg_mode, reduction="mean", sampler=smp, n_neg=w.K)
+    smp.stream = 5            # next step's number: must not reach the pending backward call
+    loss.backward()
+    ids = S.sample_negatives(S.UNIFORM, 31337, 4, w.N, w.K, w.V, per_position=(w.neg_mode == NEG_PER_POSITION))
+    ref = O.run_workload(dataclasses.replace(w, neg=ids), g=w.g.astype(np.float64))
+    valid = w.mask != 0
+    ref_mean = float(ref.loss[valid].mean())
+    assert abs(float(loss.detach()) - ref_mean) <= tol * max(abs(ref_mean), float(np.abs(ref.lse[valid]).mean()))
+    assert tensor_rel(H.grad.float().cpu().numpy(), ref.dH) <= tol
+    assert tensor_rel(E.grad.float().cpu().numpy(), ref.dE) <= tol
