@@ -90,7 +90,9 @@ typedef struct {
 /* Bytes of device workspace both calls need for this descriptor.  Returns 0 for an invalid descriptor.
  *   shared / full mode, bf16:  20 bytes per position (compaction, collision counts, coefficients), plus partial
  *                              results of split launches: 8 bytes per position and forward split, and, for batches
- *                              of at most 40,960 positions, 4 d bytes per position and dH split;
+ *                              of at most 40,960 positions, 4 d bytes per position and dH split; hidden size 256 and
+ *                              more than 65,536 positions: 64 MiB of partial dH rows for the split of the last round
+ *                              of blocks;
  *   per-position mode:         12 bytes per (position, negative) pair for the inverted index that turns the dE
  *                              scatter into a gather (pairs sorted by item) and 1/8 byte per pair for the work
  *                              list of items sampled very often, 4 bytes per table row, 4 per position;

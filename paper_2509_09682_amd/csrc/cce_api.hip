@@ -71,7 +71,11 @@ Layout make_layout(const cce_desc *d)
     L.de_const = off; off += align256((size_t)N * 8);
     L.part_m = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
     L.part_s = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
-    L.part_dH = off;  off += (sx > 1) ? align256((size_t)sx * N * d->d * 4) : 0;
+    {
+        const size_t split_bytes = (sx > 1) ? (size_t)sx * N * d->d * 4 : 0, tail_bytes = tile_tail_partial_bytes(N, d->d);
+        L.part_dH = off;
+        off += align256(split_bytes > tail_bytes ? split_bytes : tail_bytes);
+    }
     L.total = off;
     return L;
 }

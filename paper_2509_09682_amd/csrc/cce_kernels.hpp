@@ -50,6 +50,9 @@ struct TileArgs {
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
     int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
     float filter_log2;           // backward, gradient filtering: log2 of the threshold; -inf = off
+    int32_t tail_slots;          // dH pass, > 0: blocks the chip holds at once; the position blocks of the last, partly filled
+                                 // round split the candidate range among the idle block slots (planned on the device from
+                                 // the count of valid positions), partial rows in part_dH, summed by the tail merge
     int32_t g_separate;          // backward: coef and de_const[0] are what the FORWARD pass left (no upstream gradient in
                                  // them): the scatter multiplies by g itself and the dE pass streams g by row number
 };
@@ -94,6 +97,7 @@ hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a, const TileArgs *sc
 hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream);
 
 bool tile_supports_d(int d);
+size_t tile_tail_partial_bytes(int64_t N, int d);  // partial dH rows of the last-round split (0: not used for this shape)
 hipError_t launch_prep(const PrepArgs &p, hipStream_t stream);
 hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 

@@ -176,6 +176,37 @@ struct TileGeom {
     static constexpr int EPI_OWN = (MODE == MODE_DE && !EPI_IN_TILES) ? EPI_BYTES / 4 : 4;  // floats
 };
 
+// ---------------------------------------------------------------------------------------------------------------------
+// Last-round split of the dH pass.  With one block per compute unit and equal blocks, n_xb position blocks take
+// ceil(n_xb / slots) rounds, and a last round of a few blocks costs as much as a full one (c5: 600 blocks on 256
+// slots, 3 rounds for 2.34 rounds of work).  The blocks of a last round that fills at most half the chip split the
+// candidate range S ways instead (S = slots / tail, at most kTailMaxSplits), write partial rows, and a small merge
+// adds them up.  The count of valid positions is only known on the device, so every block derives the same plan from
+// it: blocks [0, F) are whole, block F + k is split k % S of position block F + k / S.
+constexpr int kTailMaxSplits = 4;
+constexpr int64_t kTailRows = 65536;  // rows of the partial buffer: S * tail blocks <= slots, slots * rows per block <= this
+struct TailPlan {
+    int64_t whole;  // F: position blocks that run unsplit
+    int64_t tail;   // position blocks of the last round
+    int splits;     // S
+};
+__device__ __forceinline__ TailPlan tail_plan(int64_t n_xb, int slots)
+{
+    TailPlan p;
+    p.whole = (n_xb / slots) * slots;
+    p.tail = n_xb - p.whole;
+    p.splits = 1;
+    if (p.tail > 0 && p.tail * 2 <= slots) {
+        const int s = (int)(slots / p.tail);
+        p.splits = s < kTailMaxSplits ? s : kTailMaxSplits;
+    }
+    if (p.splits == 1) {  // nothing to gain: every block whole
+        p.whole = n_xb;
+        p.tail = 0;
+    }
+    return p;
+}
+
 template <int D, int MODE, int BY, int NW, int XG, int NBUF, int DS, bool FILTER = false>
 __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_id, uint16_t *const buf0, uint16_t *const buf1,
                                           uint16_t *const buf2, uint16_t *const buf3, float *const epi_own)
@@ -263,8 +294,20 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     const int64_t n_x = (MODE == MODE_DE) ? a.n_cols : n_pos;
     const int64_t n_y = (MODE == MODE_DE) ? n_pos : a.n_cols;
-    const int split = (int)(bid % a.splits);
-    const int64_t xb = bid / a.splits;
+    int split = (int)(bid % a.splits), splits = a.splits;
+    int64_t xb = bid / a.splits;
+    int64_t part_rows = a.N, part_x0 = 0;  // partial dH rows of split runs: rows per split, first position filed there
+    if (MODE == MODE_DH && a.tail_slots > 0) {  // last-round split, planned from the device-side count (a.splits == 1)
+        const TailPlan tp = tail_plan((n_x + XPB - 1) / XPB, a.tail_slots);
+        if (bid >= tp.whole) {
+            xb = tp.whole + (bid - tp.whole) / tp.splits;
+            split = (int)((bid - tp.whole) % tp.splits);
+            splits = tp.splits;
+            part_rows = tp.tail * XPB;
+            part_x0 = tp.whole * XPB;
+            if (bid >= tp.whole + tp.tail * tp.splits) return;
+        }
+    }
     if (xb * XPB >= n_x) return;  // whole block past the end (the grid is sized for the unmasked N)
 
     const uint16_t *Xbase = (MODE == MODE_DE) ? a.E : a.H;
@@ -298,8 +341,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 
     // ---- range of streamed tiles of this split
     const int64_t n_tiles = (n_y + BY - 1) / BY;
-    const int64_t t_begin = n_tiles * split / a.splits;
-    const int64_t t_end = n_tiles * (split + 1) / a.splits;
+    const int64_t t_begin = n_tiles * split / splits;
+    const int64_t t_end = n_tiles * (split + 1) / splits;
 
     f32x16 acc[XG][MODE == MODE_FWD ? 1 : MBH];
     if (MODE != MODE_FWD) {
@@ -889,9 +932,9 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 #pragma unroll
         for (int g = 0; g < XG; ++g) {
             const int64_t x = xb * XPB + (xgrp * XG + g) * 32 + lo;
-            if (a.splits > 1) {
+            if (splits > 1) {
                 if (x_ok[g]) {
-                    float *dst = a.part_dH + ((int64_t)split * a.N + x) * D;
+                    float *dst = a.part_dH + ((int64_t)split * part_rows + (x - part_x0)) * D;
 #pragma unroll
                     for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
@@ -1220,14 +1263,25 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(TileArgs a)
     }
 }
 
-template <int D>
+// TAIL_XPB > 0: the merge of the last-round split of the dH pass (position blocks of TAIL_XPB rows), same plan as there.
+template <int D, int TAIL_XPB = 0>
 __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
 {
     constexpr int LPR = D / 8;  // lanes per position, 8 columns each
     static_assert(64 % LPR == 0 || LPR % 64 == 0, "row must tile the wavefront");
     constexpr int PPB = 256 / LPR;
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
-    const int64_t x = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+    int64_t x = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+    int64_t part_rows = a.N, part_x0 = 0;
+    int splits = a.splits;
+    if (TAIL_XPB > 0) {
+        const TailPlan tp = tail_plan((n_pos + TAIL_XPB - 1) / TAIL_XPB, a.tail_slots);
+        part_rows = tp.tail * TAIL_XPB;
+        part_x0 = tp.whole * TAIL_XPB;
+        splits = tp.splits;
+        if (x >= part_rows) x = n_pos;  // nothing to merge here
+        else x += part_x0;
+    }
     const int c = threadIdx.x % LPR;
     const bool ok = x < n_pos;
     const int64_t row = ok ? pos_row(a, x) : 0;
@@ -1240,9 +1294,9 @@ __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
         load8(a.E + (int64_t)a.tgt[row] * D + c * 8, e);
 #pragma unroll
         for (int t = 0; t < 8; ++t) op = fmaf(h[t], e[t], op);
-        for (int sp = 0; sp < a.splits; ++sp) {
+        for (int sp = 0; sp < splits; ++sp) {
             float v[8];
-            load8(a.part_dH + ((int64_t)sp * a.N + x) * D + c * 8, v);
+            load8(a.part_dH + ((int64_t)sp * part_rows + (x - part_x0)) * D + c * 8, v);
 #pragma unroll
             for (int t = 0; t < 8; ++t) sum[t] += v[t];
         }
@@ -1333,8 +1387,14 @@ template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 
 hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
 {
     static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>, NW * 64);
-    const int64_t blocks = plan_tile_grid<MODE>(a, n_x, (NW / DS) * XG * 32, NW * 64, slots);
+    constexpr int XPB = (NW / DS) * XG * 32;
+    int64_t blocks = plan_tile_grid<MODE>(a, n_x, XPB, NW * 64, slots);
     if (blocks == 0) return hipSuccess;
+    a.tail_slots = 0;
+    if (MODE == MODE_DH && D > 128 && a.splits == 1 && n_x > kTailRows && (int64_t)slots * XPB <= kTailRows) {
+        a.tail_slots = slots;  // last-round split: at most `slots` blocks more than position blocks
+        blocks += slots;
+    }
     ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
@@ -1415,6 +1475,15 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
             if constexpr (D > 128) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B, true>(a, a.N, stream);
             else e = hipErrorInvalidValue;  // smaller hidden sizes filter in the fused launch
         } else if (!done) e = launch_tile_kernel<D, MODE_DH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
+        if constexpr (D > 128) {
+            if (e == hipSuccess && a.tail_slots > 0) {  // rows of the split last round: at most half the chip's blocks
+                constexpr int PPB = 256 / (D / 8), XPB_L = NW_L * 32;
+                const int64_t rows = (int64_t)(a.tail_slots / 2) * XPB_L;
+                ProfScope prof(PROF_DH_MERGE, stream);
+                hipLaunchKernelGGL((dh_merge_kernel<D, XPB_L>), dim3((unsigned)((rows + PPB - 1) / PPB)), dim3(256), 0, stream, a);
+                e = hipGetLastError();
+            }
+        }
         if (e == hipSuccess && a.splits > 1) {
             constexpr int PPB = 256 / (D / 8);
             ProfScope prof(PROF_DH_MERGE, stream);
@@ -1484,6 +1553,7 @@ __global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
 }
 
 bool tile_supports_d(int d) { return d == 64 || d == 128 || d == 256; }
+size_t tile_tail_partial_bytes(int64_t N, int d) { return (d > 128 && N > kTailRows) ? (size_t)kTailRows * d * 4 : 0; }
 
 hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream)
 {

@@ -404,3 +404,18 @@ def test_per_position_negatives_with_items_sampled_very_often(case):
     counts = np.bincount(w.neg[w.mask != 0].ravel(), minlength=w.V)
     assert counts.max() > 600 and (case == "all_hot" or (counts <= 4).sum() > 100)   # one lane group walks 256 pairs
     check_against_oracle(w, _run(w), 2e-5)
+
+
+@pytest.mark.parametrize("batch,pad", [(357, "right"), (264, "none"), (460, "bernoulli"), (400, "none")])
+def test_last_round_of_position_blocks_splits_the_candidates(batch, pad):
+    """d = 256 with more position blocks than the chip holds at once: the blocks of the last, partly filled round split
+    the candidate range and a merge adds the partial dH rows (planned on the device from the count of valid positions).
+    Cases: last rounds of 63, 8 and 88 blocks on 256 slots (split 4, 4 and 2 ways; with 70 candidates = 3 tiles some
+    splits are empty), and one of 144 blocks, which stays whole."""
+    w = make_workload("tail", batch, 256, 256, 3000, 70, "bf16", NEG_SHARED, 41 + batch, g_kind="random", tgt_dist="zipf",
+                      pad=pad, pad_p=0.25, pad_len_lo=200)
+    assert w.n_valid > 65536
+    print("valid positions", w.n_valid, "position blocks", -(-w.n_valid // 256))
+    check_against_oracle(w, _run(w), TOL_BF16)
+    out = _run(w, reuse_prep=True, dH_dtype=__import__("paper_2509_09682_amd").CCE_BF16)
+    check_against_oracle(w, out, TOL_BF16)
