@@ -1359,8 +1359,10 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_me
 }
 
 // Split factor and leading blocks of one pass; returns the number of blocks of its grid (0: nothing to do).
+// fine: the pass shares its launch with another role that fills most block slots; if it splits at all, it splits as
+// finely as allowed, so that its blocks fill the gaps (c4: the fused backward launch 704 -> 671 us with 16 instead of 10).
 template <int MODE>
-int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots)
+int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots, bool fine = false)
 {
     const int64_t xblocks = (n_x + xpb - 1) / xpb;
     if (xblocks == 0) return 0;
@@ -1370,7 +1372,9 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
         const int cap = (int)(a.N * 5e-4) < 8 ? 8 : (int)(a.N * 5e-4);
         if (a.splits > cap) a.splits = cap;
     }
+    const int max_splits = a.splits;
     a.splits = pick_splits(xblocks, a.splits, slots, MODE == MODE_FWD);
+    if (fine && a.splits > 1) a.splits = max_splits;
     int64_t blocks = xblocks * a.splits;
     if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
         a.pos_blocks = (a.N + kPosChunk - 1) / kPosChunk;
@@ -1406,7 +1410,7 @@ hipError_t launch_bwd_kernel(TileArgs &a_dh, TileArgs &a_de, hipStream_t stream)
     constexpr int BY = 8192 / D, NBUF = 4;
     static const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>, 256);
     const int64_t de_blocks = plan_tile_grid<MODE_DE>(a_de, a_de.n_cols, 4 * XG_DE * 32, 256, slots);
-    const int64_t dh_blocks = plan_tile_grid<MODE_DH>(a_dh, a_dh.N, 4 * XG_DH * 32, 256, slots);
+    const int64_t dh_blocks = plan_tile_grid<MODE_DH>(a_dh, a_dh.N, 4 * XG_DH * 32, 256, slots, true);
     if (de_blocks + dh_blocks == 0) return hipSuccess;
     ProfScope prof(PROF_TILE_BWD, stream);
     hipLaunchKernelGGL((tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>), dim3((unsigned)(de_blocks + dh_blocks)), dim3(256), 0, stream,
