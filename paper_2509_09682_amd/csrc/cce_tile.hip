@@ -1309,7 +1309,7 @@ __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
         const float pp = __builtin_amdgcn_exp2f((op - a.lse_in[row]) * kLog2e);
         const float cpos = w * pp - 1.f;
         const float g = a.g ? a.g[row] : 1.f;
-        if (c == 0) a.coef[row] = g * cpos;
+        if (c == 0 && a.write_consts) a.coef[row] = g * cpos;  // for a scatter in a later launch; the fused launch has its own
         float v[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] = g * fmaf(cpos, e[t], sum[t]);

@@ -111,6 +111,19 @@ def test_backward_reusing_the_forward_preparation(d):
     assert tensor_rel(a["dE"], b["dE"]) <= 1e-5      # atomics: same terms, order may differ
 
 
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_two_backward_calls_reuse_one_forward_preparation(d):
+    """What the forward call files for the backward pass survives a backward call: a second one on the same workspace
+    (few positions and many candidates: the dH role splits and merges) adds the same gradient again."""
+    import paper_2509_09682_amd as P
+
+    w = make_workload(f"twice_d{d}", 7, 90, d, 6000, 0, "bf16", NEG_FULL, 99 + d, pad="bernoulli", pad_p=0.2, g_kind="random",
+                      e_sigma=0.1, tgt_dist="zipf")
+    out = _run(w, algo=P.CCE_ALGO_TILE, reuse_prep=True, repeat_backward=2)
+    out["dE"] = out["dE"] * 0.5
+    check_against_oracle(w, out, TOL_BF16)
+
+
 @pytest.mark.parametrize("d", [64, 256])
 def test_forward_and_dH_are_bitwise_reproducible(d):
     """No atomics feed loss, lse or dH: two runs on the same inputs must agree bit for bit (a vector instruction that
@@ -227,7 +240,7 @@ def test_index_validation_skips_bad_ids_and_reports():
 def test_full_size_configs_against_full_oracle(idx):
     """The benchmark shapes, every output element held against the oracle (the oracle finishes these in seconds)."""
     w = config(idx)
-    out = _run(w)
+    out = _run(w, reuse_prep=True)   # as bench.py runs it: the backward call reuses the forward call's preparation
     tol = TOL_BF16
     errs = check_against_oracle(w, out, tol)
     # zero column sum of dE: sum_v dE[v,:] = sum_i g_i (sum_j p_ij - 1) h_i = 0
@@ -343,13 +356,15 @@ def test_full_size_large_configs_on_sampled_positions(idx, n_sample):
 
     H, E, tgt, neg, mask = to_device(w)
     desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_BF16, w.neg_mode, mask_target_collisions=w.mask_collisions)
+    desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_BF16, w.neg_mode, mask_target_collisions=w.mask_collisions,
+                           reuse_forward_prep=1)   # as in bench.py
     ws = P.new_workspace(desc)
     loss = torch.full((w.N,), float("nan"), device="cuda")
     lse = torch.full((w.N,), float("nan"), device="cuda")
     dH = torch.full((w.N, w.d), float("nan"), device="cuda")
     dE = torch.zeros((w.V, w.d), device="cuda")
     P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
-    P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, torch.from_numpy(g).cuda(), dH, dE, ws)
+    P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, torch.from_numpy(g).cuda(), dH, dE, ws)
     torch.cuda.synchronize()
 
     ref = O.run_workload(w, g=g.astype(np.float64), sel=S, want_dE="compact")
@@ -374,7 +389,7 @@ def test_full_size_large_configs_on_sampled_positions(idx, n_sample):
 
     # ---- run 2: the benchmark's grad_loss
     dE.zero_()
-    P.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, torch.from_numpy(w.g).cuda(), dH, dE, ws)
+    P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, torch.from_numpy(w.g).cuda(), dH, dE, ws)
     torch.cuda.synchronize()
     col = dE.double().sum(0).abs().max().item()
     scale = dE.double().abs().sum(0).max().item()
