@@ -72,7 +72,9 @@ typedef struct {
     int32_t algo;                   /* cce_algo */
     int32_t reuse_forward_prep;     /* backward only, 1: the caller vouches that the workspace still holds what the
                                        forward call with this descriptor and the same tgt / neg / mask contents left
-                                       there (nothing else wrote to it since), so the compaction of padded positions,
+                                       there (nothing else wrote to it since: no other forward call, no backward call
+                                       without this flag; backward calls with it may repeat), so the compaction of
+                                       padded positions,
                                        the collision counts and (hidden sizes up to 128, grad_loss given) the
                                        per-position constants that the forward call files for the backward pass are
                                        not recomputed; lse must then be the forward call's own output.  0: no

@@ -69,6 +69,8 @@ class _CceNegLoss(torch.autograd.Function):
         # the compaction the forward call left in the workspace is reused unless another forward call of the same
         # shape has overwritten it since (two loss terms in one graph)
         reuse = 1 if _last_forward.get(ctx.key) == ctx.serial else 0
+        if not reuse:
+            _last_forward[ctx.key] = None   # this call rewrites the workspace: it no longer holds any forward call's state
         desc = B.make_desc(N, V, d, K, dt, neg_mode, reuse_forward_prep=reuse, filter_eps=filter_eps, **kw)
         if ctx.sampler is not None:
             B.cce_neg_backward_sampled(desc, ctx.sampler, H, E, tgt, mask, lse, g, dH, dE, ctx.ws)

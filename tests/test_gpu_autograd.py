@@ -75,6 +75,29 @@ def test_two_losses_of_one_shape_in_one_graph():
     assert e_dH <= 2e-2 and e_dE <= 2e-2
 
 
+def test_backward_order_against_forward_order():
+    """Forward a, forward b, then backward a BEFORE backward b: a's backward call rewrites the shared workspace, so
+    b's must not trust it either."""
+    import torch
+
+    import paper_2509_09682_amd as P
+
+    wa = config(2, scale=0.03, g_kind="mean")
+    wb_src = make_workload("b", wa.batch, wa.seq_len, wa.d, wa.V, wa.K, "bf16", NEG_SHARED, 778, tgt_dist="zipf",
+                           pad="bernoulli", pad_p=0.3)
+    wb = dataclasses.replace(wb_src, H=wa.H, E=wa.E)
+    H, E, tgt_a, neg_a, mask_a = _leaves(wa)
+    tgt_b, neg_b, mask_b = (torch.from_numpy(x).cuda() for x in (wb.tgt, wb.neg, wb.mask))
+    la = P.cce_neg_loss(H, E, tgt_a, neg_a, mask_a, reduction="sum")
+    lb = P.cce_neg_loss(H, E, tgt_b, neg_b, mask_b, reduction="sum")
+    la.backward()
+    lb.backward()
+    ra = O.run_workload(wa, g=np.ones(wa.N))
+    rb = O.run_workload(wb, g=np.ones(wb.N))
+    assert tensor_rel(H.grad.float().cpu().numpy(), ra.dH + rb.dH) <= 2e-2
+    assert tensor_rel(E.grad.float().cpu().numpy(), ra.dE + rb.dE) <= 2e-2
+
+
 def test_reductions_agree():
     import paper_2509_09682_amd as P
 
