@@ -215,7 +215,25 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
     const int64_t id0 = (int64_t)b << kBucketShift;
     for (int k = threadIdx.x; k < kBucketIds; k += kScanThreads) hist[k] = 0;
     __syncthreads();
-    for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) atomicAdd(&hist[a.tmp[e].x - (int32_t)id0], 1);
+    // A hot item owns most entries of its bucket, and 64 lanes adding to one LDS word take 64 turns: in a crowded bucket
+    // the lanes that hold the same id as the first active lane are counted with one ballot and added by that lane alone.
+    const bool crowded = re - rb > 16 * kBucketIds;  // block-uniform; ordinary buckets take the plain loops
+    if (!crowded)
+        for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) atomicAdd(&hist[a.tmp[e].x - (int32_t)id0], 1);
+    for (int32_t e0 = rb; crowded && e0 < re; e0 += kScanThreads) {
+        const int32_t e = e0 + (int32_t)threadIdx.x;
+        const bool in = e < re;
+        const int32_t k = in ? a.tmp[e].x - (int32_t)id0 : -1;
+        const int32_t lead = __builtin_amdgcn_readfirstlane(k);
+        const uint64_t same = __ballot(in && k == lead);
+        if (in) {
+            if (k == lead) {
+                if ((same & ((1ull << (threadIdx.x & 63)) - 1ull)) == 0) atomicAdd(&hist[k], (int32_t)__popcll(same));
+            } else {
+                atomicAdd(&hist[k], 1);
+            }
+        }
+    }
     __syncthreads();
     // exclusive scan over the counts: consecutive ids per thread
     int32_t v[kBucketIds / kScanThreads], sum = 0;
@@ -234,10 +252,31 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
         if (id0 + k < a.V) a.cursor[id0 + k] = rb + run;  // END of the item's segment
     }
     __syncthreads();
-    for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) {
-        const int2 t = a.tmp[e];
-        const int32_t slot = atomicAdd(&hist[t.x - (int32_t)id0], 1);
-        a.pairs[rb + slot] = t.y;
+    if (!crowded)
+        for (int32_t e = rb + (int32_t)threadIdx.x; e < re; e += kScanThreads) {
+            const int2 t = a.tmp[e];
+            const int32_t slot = atomicAdd(&hist[t.x - (int32_t)id0], 1);
+            a.pairs[rb + slot] = t.y;
+        }
+    for (int32_t e0 = rb; crowded && e0 < re; e0 += kScanThreads) {
+        const int32_t e = e0 + (int32_t)threadIdx.x;
+        const bool in = e < re;
+        const int2 t = in ? a.tmp[e] : make_int2(-1, 0);
+        const int32_t k = in ? t.x - (int32_t)id0 : -1;
+        const int32_t lead = __builtin_amdgcn_readfirstlane(k);
+        const uint64_t same = __ballot(in && k == lead);
+        const int lane = threadIdx.x & 63;
+        int32_t slot = 0;
+        if (in && k == lead) {  // one returning add for all of them, ranks by lane order
+            const int first = __ffsll((unsigned long long)same) - 1;
+            int32_t base = 0;
+            if (lane == first) base = atomicAdd(&hist[k], (int32_t)__popcll(same));
+            base = __shfl(base, first, 64);
+            slot = base + (int32_t)__popcll(same & ((1ull << lane) - 1ull));
+        } else if (in) {
+            slot = atomicAdd(&hist[k], 1);
+        }
+        if (in) a.pairs[rb + slot] = t.y;
     }
 }
 
