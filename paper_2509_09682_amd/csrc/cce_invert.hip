@@ -280,45 +280,78 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
     }
 }
 
-// Walks the positions filed in pairs[r, r_end) for the item whose row e the lane group holds, four at a time:
+// A row chunk of 8 elements as it comes from memory; bf16 rows stay packed (4 registers) until they are used, so that
+// twice as many rows can be in flight per wavefront as with widened copies.
+template <typename T> struct RawChunk;
+template <> struct RawChunk<uint16_t> {
+    uint4 v;
+    static constexpr int kInFlight = 8;
+    __device__ __forceinline__ void load(const uint16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void clear() { v = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void widen(float (&h)[8]) const
+    {
+        h[0] = bf16_lo(v.x); h[1] = bf16_hi(v.x);
+        h[2] = bf16_lo(v.y); h[3] = bf16_hi(v.y);
+        h[4] = bf16_lo(v.z); h[5] = bf16_hi(v.z);
+        h[6] = bf16_lo(v.w); h[7] = bf16_hi(v.w);
+    }
+};
+template <> struct RawChunk<float> {
+    float4 a, b;
+    static constexpr int kInFlight = 4;
+    __device__ __forceinline__ void load(const float *p)
+    {
+        a = reinterpret_cast<const float4 *>(p)[0];
+        b = reinterpret_cast<const float4 *>(p)[1];
+    }
+    __device__ __forceinline__ void clear() { a = b = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void widen(float (&h)[8]) const
+    {
+        h[0] = a.x; h[1] = a.y; h[2] = a.z; h[3] = a.w;
+        h[4] = b.x; h[5] = b.y; h[6] = b.z; h[7] = b.w;
+    }
+};
+
+// Walks the positions filed in pairs[r, r_end) for the item whose row e the lane group holds, kInFlight at a time:
 // recomputes each score against the hidden state (L2-resident), forms g exp(o - lse) and adds G h to acc.
 // Every lane of the wavefront calls it (the loop condition is a wavefront vote, the scalar products use shuffles).
 template <typename T, int LPR>
 __device__ __forceinline__ void walk_segment(const InvertArgs &a, const float (&e)[8], int32_t r, int32_t r_end, bool col_ok,
                                              int c, float (&acc)[8])
 {
+    constexpr int U = RawChunk<T>::kInFlight;
     const T *Hp = static_cast<const T *>(a.H);
     while (__any(r < r_end)) {
-        int32_t pos[4];
-        float h[4][8], lse[4], g[4];
+        int32_t pos[U];
+        RawChunk<T> raw[U];
+        float lse[U], g[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            pos[u] = (r + u < r_end) ? a.pairs[r + u] : -1;
+        for (int u = 0; u < U; ++u) pos[u] = (r + u < r_end) ? a.pairs[r + u] : -1;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) h[u][t] = 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
+            raw[u].clear();
             lse[u] = 0.f;
             g[u] = 0.f;
             if (pos[u] >= 0) {
-                if (col_ok) load8(Hp + pos[u] * (int64_t)a.d + c * 8, h[u]);
+                if (col_ok) raw[u].load(Hp + pos[u] * (int64_t)a.d + c * 8);
                 lse[u] = a.lse_in[pos[u]];
                 g[u] = a.g ? a.g[pos[u]] : 1.f;
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < U; ++u) {
+            float h[8];
+            raw[u].widen(h);
             float part = 0.f;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) part = fmaf(h[u][t], e[t], part);
+            for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[t], part);
 #pragma unroll
             for (int off = 1; off < LPR; off <<= 1) part += __shfl_xor(part, off, 64);  // partners share the item
             const float G = (pos[u] >= 0) ? g[u] * fast_exp(part - lse[u]) : 0.f;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, h[u][t], acc[t]);
+            for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, h[t], acc[t]);
         }
-        r += 4;
+        r += U;
     }
 }
 
