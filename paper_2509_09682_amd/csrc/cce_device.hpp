@@ -65,6 +65,38 @@ __device__ __forceinline__ void load8(const uint16_t *p, float (&v)[8])
     v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z);
     v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
 }
+// A row chunk of 8 elements as it comes from memory; bf16 rows stay packed (4 registers) until they are used, so that
+// twice as many rows can be in flight per wavefront as with widened copies.
+template <typename T> struct RawChunk;
+template <> struct RawChunk<uint16_t> {
+    uint4 v;
+    static constexpr int kInFlight = 8;
+    __device__ __forceinline__ void load(const uint16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void clear() { v = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void widen(float (&h)[8]) const
+    {
+        h[0] = bf16_lo(v.x); h[1] = bf16_hi(v.x);
+        h[2] = bf16_lo(v.y); h[3] = bf16_hi(v.y);
+        h[4] = bf16_lo(v.z); h[5] = bf16_hi(v.z);
+        h[6] = bf16_lo(v.w); h[7] = bf16_hi(v.w);
+    }
+};
+template <> struct RawChunk<float> {
+    float4 a, b;
+    static constexpr int kInFlight = 4;
+    __device__ __forceinline__ void load(const float *p)
+    {
+        a = reinterpret_cast<const float4 *>(p)[0];
+        b = reinterpret_cast<const float4 *>(p)[1];
+    }
+    __device__ __forceinline__ void clear() { a = b = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void widen(float (&h)[8]) const
+    {
+        h[0] = a.x; h[1] = a.y; h[2] = a.z; h[3] = a.w;
+        h[4] = b.x; h[5] = b.y; h[6] = b.z; h[7] = b.w;
+    }
+};
+
 __device__ __forceinline__ float load1(const float *p) { return *p; }
 __device__ __forceinline__ float load1(const uint16_t *p) { return __uint_as_float(static_cast<uint32_t>(*p) << 16); }
 

@@ -19,7 +19,9 @@ namespace cce {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 4;
+// load instructions in flight per wavefront: bf16 rows stay packed in registers until they are used, so eight fit where
+// four widened ones would
+template <typename T> constexpr int unroll_of() { return RawChunk<T>::kInFlight; }
 constexpr int kWindow = 256;  // per-position negatives: candidate ids a wavefront stages per refill of its LDS window
 
 // Where the ids of the negatives come from.
@@ -102,6 +104,7 @@ template <typename T, int LPR, int IDS>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params p)
 {
     constexpr int RPI = 64 / LPR;  // candidate rows per wavefront step
+    constexpr int kUnroll = unroll_of<T>();
     static_assert(kWindow % (RPI * kUnroll) == 0, "a step never straddles two windows");
     __shared__ int32_t window[IDS != IDS_DIRECT ? kWavesPerBlock : 1][IDS != IDS_DIRECT ? kWindow : 1];
     int32_t *win = window[IDS != IDS_DIRECT ? (threadIdx.x >> 6) : 0];
@@ -141,19 +144,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params 
     for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
         if (IDS != IDS_DIRECT && (j0 & (kWindow - 1)) == 0) refill_window<IDS>(p, i, j0, win);
         Cand cd[kUnroll];
-        float e[kUnroll][8];
+        RawChunk<T> raw[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             cd[u] = candidate<IDS>(p, i, j0 + u * RPI + grp, n_cand, ti, bad, win);
-#pragma unroll
-            for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
-            if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
+            raw[u].clear();
+            if (cd[u].live && col_ok) raw[u].load(Ep + cd[u].id * (int64_t)p.d + c * 8);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
+            float e[8];
+            raw[u].widen(e);
             float part = 0.f;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[u][t], part);
+            for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[t], part);
             const float o = group_sum<LPR>(part);
             if (cd[u].live) {
                 if (cd[u].is_pos) o_pos = o;
@@ -187,6 +191,7 @@ template <typename T, int LPR, bool ATOMIC_DE, int IDS>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params p)
 {
     constexpr int RPI = 64 / LPR;
+    constexpr int kUnroll = unroll_of<T>();
     __shared__ int32_t window[IDS != IDS_DIRECT ? kWavesPerBlock : 1][IDS != IDS_DIRECT ? kWindow : 1];
     int32_t *win = window[IDS != IDS_DIRECT ? (threadIdx.x >> 6) : 0];
     const int lane = threadIdx.x & 63;
@@ -225,25 +230,26 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void bwd_gather_kernel(Params 
         for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
             if (IDS != IDS_DIRECT && (j0 & (kWindow - 1)) == 0) refill_window<IDS>(p, i, j0, win);
             Cand cd[kUnroll];
-            float e[kUnroll][8];
+            RawChunk<T> raw[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 cd[u] = candidate<IDS>(p, i, j0 + u * RPI + grp, n_cand, ti, bad, win);
-#pragma unroll
-                for (int t = 0; t < 8; ++t) e[u][t] = 0.f;
-                if (cd[u].live && col_ok) load8(Ep + cd[u].id * (int64_t)p.d + c * 8, e[u]);
+                raw[u].clear();
+                if (cd[u].live && col_ok) raw[u].load(Ep + cd[u].id * (int64_t)p.d + c * 8);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
+                float e[8];
+                raw[u].widen(e);
                 float part = 0.f;
 #pragma unroll
-                for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[u][t], part);
+                for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[t], part);
                 const float o = group_sum<LPR>(part);
                 if (cd[u].live) {
                     const float pj = fast_exp(o - lse);
                     const float G = gi * (pj - (cd[u].is_pos ? 1.f : 0.f));
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, e[u][t], acc[t]);
+                    for (int t = 0; t < 8; ++t) acc[t] = fmaf(G, e[t], acc[t]);
                     if (cd[u].is_pos && p.coef && c == 0) p.coef[i] = G;
                     if (ATOMIC_DE && (cd[u].is_pos ? !p.skip_pos_dE : !p.skip_neg_dE)) {
                         float *row = p.dE + cd[u].id * (int64_t)p.d;
