@@ -180,6 +180,10 @@ __global__ __launch_bounds__(kThreads) void part_count_kernel(InvertArgs a)
     for_live_pairs(a, (int64_t)blockIdx.x, [&](int32_t id, int32_t) { atomicAdd(&hist[id >> kBucketShift], 1); });
     __syncthreads();
     for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) a.part_hist[(int64_t)b * gridDim.x + blockIdx.x] = hist[b];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {  // two words the later kernels of this call expect to be zero
+        *a.part_total = 0;   // last entry of the scanned array: receives the grand total
+        *a.hot_count = 0;    // work list of the item pass
+    }
 }
 
 // D_SC != 0: the first sc_blocks blocks scatter the gradient rows of the correct items (hidden size D_SC) instead;
@@ -416,8 +420,10 @@ hipError_t launch_item_dE(const InvertArgs &a, hipStream_t stream)
 {
     constexpr int items_per_block = (kThreads / 64) * (64 / LPR);
     ProfScope prof(PROF_ITEM_DE, stream);
-    hipError_t e = launch_fill_zero(a.hot_count, 1, stream);
-    if (e != hipSuccess) return e;
+    if (!invert_partitioned(a.V)) {  // the partitioned index build has cleared the work-list counter on its way
+        const hipError_t e = launch_fill_zero(a.hot_count, 1, stream);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL((item_dE_kernel<T, LPR>), dim3((unsigned)((a.V + items_per_block - 1) / items_per_block)),
                        dim3(kThreads), 0, stream, a);
     hipLaunchKernelGGL((hot_item_kernel<T, LPR>), dim3(kHotBlocks), dim3(kThreads), 0, stream, a);
@@ -484,7 +490,6 @@ hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, const TileArgs 
             const int64_t n_hist = (int64_t)a.n_buckets * a.n_part_blocks;
             a.part_total = a.part_hist + n_hist;  // one extra word: scanning n_hist + 1 entries leaves the grand total there
             hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
-            if ((e = launch_fill_zero(a.part_total, 1, stream)) != hipSuccess) return e;
             if ((e = launch_scan(a.part_hist, n_hist + 1, a.block_sums, stream)) != hipSuccess) return e;
             if (scatter) {  // the correct items' rows ride at the head of this launch
                 const int64_t sc_blocks = (scatter->N + kPosChunk - 1) / kPosChunk;
