@@ -39,6 +39,10 @@ enum { MODE_FWD = 0, MODE_DH = 1, MODE_DE = 2 };
 // Compile-time tags: a full streamed tile, or the short last tile whose missing rows are masked.
 struct Full { static constexpr bool value = false; };
 struct Ragged { static constexpr bool value = true; };
+// Forward softmax of a tile: with the running maximum kept up to date (Exact), or against the maximum as it stood when
+// the tile began (Lazy: no maximum, no rescaling; the caller repeats the tile exactly if a sum overflowed).
+struct Exact { static constexpr bool lazy = false; };
+struct Lazy { static constexpr bool lazy = true; };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {
@@ -509,10 +513,23 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(op[kk]), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
     };
     // accumulator register q of lane (lo, hi) holds streamed row y = sb*32 + (q/4)*8 + hi*4 + q%4
-    auto softmax = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG], gp_t &gp, int rows_here, auto ragged_tag, bool &kept) {
+    auto softmax = [&](const uint16_t *tile, int sb, f32x16 (&sv)[XG], gp_t &gp, int rows_here, auto ragged_tag, bool &kept,
+                       auto max_tag) {
         constexpr bool RAGGED = decltype(ragged_tag)::value;
+        constexpr bool LAZY = decltype(max_tag)::lazy;
         const int rem = rows_here - sb * 32 - hi * 4;  // register q is a real row iff (q/4)*8 + q%4 < rem
-        if (MODE == MODE_FWD) {
+        if (MODE == MODE_FWD && LAZY) {
+            // Any reference keeps the sum of exponentials exact as long as nothing overflows; the one in hand saves the
+            // maximum chain and the rescaling (a fifth of the vector instructions of the forward pass).
+#pragma unroll
+            for (int g = 0; g < XG; ++g) {
+                const float ref = -run_m[g];
+                float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 16; ++q) part[q & 3] += __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, ref));
+                run_s[g] += (part[0] + part[1]) + (part[2] + part[3]);
+            }
+        } else if (MODE == MODE_FWD) {
 #pragma unroll
             for (int g = 0; g < XG; ++g) {
                 if (RAGGED) {  // rows past the end do not take part
@@ -663,7 +680,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     constexpr int NM_P = BWD ? 2 * MBH * XG : 0;  // ... of a second product
     constexpr int N_TR = 4 * MBH;                 // transpose reads of a second product
     constexpr int VALU_C = XG * (MODE == MODE_FWD ? 56 : (MODE == MODE_DH ? 42 : 58));  // vector instructions of a softmax
-    auto process_tile = [&](int64_t t, const uint16_t *tile, auto ragged_tag) {
+    auto process_tile = [&](int64_t t, const uint16_t *tile, auto ragged_tag, auto max_tag) {
         // rows of this tile that exist; only the last tile of the streamed range can be short
         const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
         if constexpr (SWP) {
@@ -688,7 +705,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 if (k + OPD < NSB) load_ops(tile, k + OPD, op[opl]);
                 if (BWD && k > 0 && kept[n]) second(tr, gp[n]);
                 if (k + 1 < NSB) mfma_scores(op[opn], sv[n]);
-                softmax(tile, k, sv[c], gp[c], rows_here, ragged_tag, kept[c]);
+                softmax(tile, k, sv[c], gp[c], rows_here, ragged_tag, kept[c], max_tag);
                 if (BWD && kept[c]) load_tr(tile, k, tr);
                 // ---- issue order of this phase
                 const int n_mfma = ((BWD && k > 0) ? NM_P : 0) + (k + 1 < NSB ? NM_S : 0);
@@ -777,14 +794,14 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     };
                     bool kept = true;
                     if (FILTER) {  // the reads wait for the verdict on the block
-                        softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
+                        softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept, max_tag);
                         if (!kept) continue;
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     read_tr_batch(0, tb[0]);
                     read_tr_batch(1, tb[1]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (!FILTER) softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
+                    if (!FILTER) softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept, max_tag);
 #pragma unroll
                     for (int b = 0; b < NB_P; ++b) {
                         __builtin_amdgcn_sched_barrier(0);
@@ -805,7 +822,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     }
                 } else {
                     bool kept = true;
-                    softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept);
+                    softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept, max_tag);
                 }
             }
         }
@@ -837,7 +854,29 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             rows_from_lds(t + PF, cur, rows);
             issue_group(t + PF, rows, nxt);
         }
-        process_tile(t, cur, Full{});
+        // d = 256: few tiles per block and a kernel at the edge of its register budget; measured slower there
+        if (MODE == MODE_FWD && D <= 128 && t != t_begin) {  // the first tile has no maximum to lean on
+            float m0[XG], s0[XG];
+            bool over = false;
+#pragma unroll
+            for (int g = 0; g < XG; ++g) {
+                m0[g] = run_m[g];
+                s0[g] = run_s[g];
+            }
+            process_tile(t, cur, Full{}, Lazy{});
+#pragma unroll
+            for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 3.0e38f);  // overflow (or NaN)
+            if (__any(over)) {
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    run_m[g] = m0[g];
+                    run_s[g] = s0[g];
+                }
+                process_tile(t, cur, Full{}, Exact{});
+            }
+        } else {
+            process_tile(t, cur, Full{}, Exact{});
+        }
         pin_results();
         wait_for_next(t);
         barrier_keep_loads();
@@ -884,7 +923,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         }
     }
     if (tail_ragged) {  // its group was issued with the others, and the last wait above was for all loads
-        process_tile(t_stop, buf_at((int)((t_stop - t_begin) % NB)), Ragged{});
+        process_tile(t_stop, buf_at((int)((t_stop - t_begin) % NB)), Ragged{}, Exact{});
         __syncthreads();  // the dE epilogue reuses the tile buffers
     }
 

@@ -434,3 +434,34 @@ def test_last_round_of_position_blocks_splits_the_candidates(batch, pad):
     check_against_oracle(w, _run(w), TOL_BF16)
     out = _run(w, reuse_prep=True, dH_dtype=__import__("paper_2509_09682_amd").CCE_BF16)
     check_against_oracle(w, out, TOL_BF16)
+
+
+@pytest.mark.parametrize("d,mode", [(64, NEG_FULL), (128, NEG_SHARED), (256, NEG_FULL)])
+def test_scores_that_outgrow_the_running_maximum_by_hundreds_of_nats(d, mode):
+    """The forward pass sums a tile's exponentials against the maximum it knew when the tile began and repeats the tile
+    exactly when that overflowed.  Here the scores of a position climb (or fall) by several hundred nats along the
+    candidate index, far beyond the range of a float exponential relative to a stale maximum."""
+    from workloads import bf16_bits_from_f32
+
+    V, K = 3000, 1500
+    w = make_workload(f"steep_d{d}", 3, 111, d, V, 0 if mode == NEG_FULL else K, "bf16", mode, 7 + d, pad="bernoulli", pad_p=0.1,
+                      g_kind="random", neg_dist="uniform")
+    rng = np.random.default_rng(d)
+    u = rng.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    slope = rng.uniform(-1.5, 1.5, size=w.N).astype(np.float32)               # climbing and falling positions
+    H = slope[:, None] * u[None, :] + 0.01 * rng.standard_normal((w.N, d)).astype(np.float32)
+    ramp = np.arange(V, dtype=np.float32) / V
+    if mode == NEG_SHARED:                                                     # make the ramp follow the candidate order
+        order = np.empty(V, np.float32)
+        order[:] = 0.5
+        order[w.neg] = np.arange(K, dtype=np.float32) / K
+        ramp = order
+    E = 400.0 * ramp[:, None] * u[None, :] + 0.01 * rng.standard_normal((V, d)).astype(np.float32)
+    w.H = bf16_bits_from_f32(H.astype(np.float32))
+    w.E = bf16_bits_from_f32(E.astype(np.float32))
+    out = _run(w)
+    assert np.all(np.isfinite(out["loss"])) and np.all(np.isfinite(out["dH"]))
+    ref = O.run_workload(w, g=w.g.astype(np.float64))
+    assert np.abs(ref.lse).max() > 300
+    check_against_oracle(w, out, TOL_BF16)
