@@ -111,3 +111,23 @@ def test_other_stream_other_negatives():
     a = run_hip_sampled(w, device_sampler(S.UNIFORM, 1, 0)[0])
     b = run_hip_sampled(w, device_sampler(S.UNIFORM, 1, 1)[0])
     assert np.mean(a["loss"] != b["loss"]) > 0.99
+
+
+def test_sampled_calls_edge_cases():
+    """K = 0 (nothing to draw: loss 0, gradients 0), every position padded, and a single position."""
+    from hip_harness import device_sampler, run_hip_sampled
+
+    smp, _ = device_sampler(S.UNIFORM, 5, 0)
+    w = _shape(40, 0, 500, NEG_PER_POSITION, d=64, dtype="bf16")
+    out = run_hip_sampled(w, smp)
+    assert np.all(out["loss"] == 0) and np.all(out["dH"] == 0) and np.all(out["dE"] == 0)
+
+    w = _shape(50, 33, 500, NEG_PER_POSITION, d=64, dtype="bf16")
+    w.mask[:] = 0
+    out = run_hip_sampled(w, smp)
+    assert np.all(out["loss"] == 0) and np.all(out["lse"] == 0) and np.all(out["dH"] == 0) and np.all(out["dE"] == 0)
+
+    for mode in (NEG_PER_POSITION, NEG_SHARED):
+        w = _shape(1, 19, 500, mode, d=128, dtype="bf16")
+        w_ref = dataclasses.replace(w, neg=_reference_ids(w, S.UNIFORM, 5, 0, None))
+        _check(w_ref, run_hip_sampled(w, smp), TOL_BF16)
