@@ -247,7 +247,6 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     static_assert(CI <= NW && NI <= NW, "every wavefront issues exactly one instruction of each kind");
     // dE epilogue: one 32 x 33 float transpose buffer per wavefront and the row numbers of the block.  They reuse the
     // first two tile buffers where those are big enough (two wavefronts' worth per buffer), else get an array.
-    constexpr int EPI_BYTES = NW * 32 * 33 * 4 + XPB * 8;
     constexpr bool EPI_IN_TILES = (MODE == MODE_DE) && (NW == 4) && (TILE * 2 >= 2 * 32 * 33 * 4 + XPB * 8);
     static_assert(NW % 2 == 0, "wavefronts pair up on the tile buffers");
 
@@ -1059,8 +1058,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void tile_kernel(TileArgs a)
 // The dH and the dE pass of one backward call in a single launch: with few positions neither pass fills the chip on
 // its own (c2: 320 + 256 blocks of one wavefront per SIMD each), and both are bound by latencies rather than by any
 // unit, so they overlap almost completely.  The dE blocks (correct-item scatter first) lead the grid, being the longer
-// ones.  Both roles share the LDS arrays; neither reads what the other writes (coef and de_const come from
-// bwd_pre_kernel).
+// ones.  Both roles share the LDS arrays; neither reads what the other writes (coef and de_const come from the
+// forward call, or from bwd_pre_kernel when its preparation is not reused).
 template <int D, int BY, int XG_DH, int XG_DE, int NBUF, bool FILTER>
 __global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArgs a_de, int64_t de_blocks)
 {
@@ -1082,7 +1081,7 @@ __global__ __launch_bounds__(256, 2) void tile_bwd_kernel(TileArgs a_dh, TileArg
         tile_body<D, MODE_DH, BY, 4, XG_DH, NBUF, 1, FILTER>(a_dh, b - de_blocks, buf0, buf1, buf2, buf3, epi_own);
 }
 
-// Per valid position, ahead of a fused backward launch: the coefficient of the correct item g (w p+ - 1) for the
+// Per valid position, ahead of a fused backward launch that does not reuse the forward call's constants: the coefficient of the correct item g (w p+ - 1) for the
 // scatter, and the exponent offset -lse log2e and g of the dE coefficients g exp(o - lse) = g 2^(o log2e - lse log2e)
 // under the compacted index.  D/8 lanes per position share the scalar product with the correct item's row.
 template <int D>
