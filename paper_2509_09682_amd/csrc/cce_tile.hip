@@ -480,13 +480,15 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     const int t_row = hi * 4 + ta;
     const int t_base0 = t_row * D + (((cb * 2 + (tb >> 1)) ^ swz<CPR>(t_row)) * 8) + (tb & 1) * 4;
     const int t_base1 = (t_base0 ^ 16) + 8 * D;
-    auto xor_bits = [&](int base, int bits) -> int {
-        if (LEAN) {  // opaque to the optimiser, so it stays inside the loop
+    // Address of element (base ^ bits) + extra behind p.  LEAN: the XOR is done on byte offsets (no shift between it and
+    // the read) by an instruction the optimiser cannot hoist out of the loop.
+    auto lds_at = [&](const uint16_t *p, int base, int bits, int extra) -> const uint16_t * {
+        if (LEAN) {
             int r;
-            asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "s"(bits), "v"(base));
-            return r;
+            asm volatile("v_xor_b32 %0, %1, %2" : "=v"(r) : "s"(bits * 2), "v"(base * 2));
+            return reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(p) + r) + extra;
         }
-        return base ^ bits;
+        return p + (base ^ bits) + extra;
     };
 
     constexpr int NSB = BY / 32;
@@ -498,7 +500,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         const uint16_t *arow = tile + sb * 32 * D;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
-            op[kk] = *reinterpret_cast<const uint4 *>(arow + xor_bits(a_base, ((kk * 2) & SM) * 8) + (kk / NA) * (NA * 16));
+            op[kk] = *reinterpret_cast<const uint4 *>(lds_at(arow, a_base, ((kk * 2) & SM) * 8, (kk / NA) * (NA * 16)));
     };
     auto mfma_scores = [&](const uint4 (&op)[KK], f32x16 (&sv)[XG]) {
 #pragma unroll
@@ -644,8 +646,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 #pragma unroll
             for (int mb = 0; mb < MBH; ++mb) {
                 const int col = (mb / NT) * (NT * 32);
-                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base0, ((mb * 4) & SM) * 8) + col));
-                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base1, ((mb * 4) & SM) * 8) + col));
+                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(lds_at(tbase, t_base0, ((mb * 4) & SM) * 8, col)));
+                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(lds_at(tbase, t_base1, ((mb * 4) & SM) * 8, col)));
                 tr[k2][mb] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
@@ -756,7 +758,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 #pragma unroll
                     for (int i = 0; i < BS; ++i) {
                         const int kk = b * BS + i;
-                        dst[i] = *reinterpret_cast<const uint4 *>(arow + xor_bits(a_base, ((kk * 2) & SM) * 8) + (kk / NA) * (NA * 16));
+                        dst[i] = *reinterpret_cast<const uint4 *>(lds_at(arow, a_base, ((kk * 2) & SM) * 8, (kk / NA) * (NA * 16)));
                     }
                 };
 #pragma unroll
@@ -786,8 +788,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                         for (int i = 0; i < BS; ++i) {
                             const int mb = (b % (MBH / BS)) * BS + i;
                             const int col = (mb / NT) * (NT * 32);
-                            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base0, ((mb * 4) & SM) * 8) + col));
-                            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tbase + xor_bits(t_base1, ((mb * 4) & SM) * 8) + col));
+                            const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(lds_at(tbase, t_base0, ((mb * 4) & SM) * 8, col)));
+                            const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(lds_at(tbase, t_base1, ((mb * 4) & SM) * 8, col)));
                             dst[i] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
                         }
                     };
