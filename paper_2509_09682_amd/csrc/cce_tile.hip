@@ -745,6 +745,9 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             // Operands are therefore read in batches of four into two alternating register sets, and every batch is
             // requested one batch of matrix instructions ahead of its use.
             constexpr int BS = (DS == 1 && BWD) ? 2 : 4;  // operands per batch: two where all output columns are held
+            // operand batches in flight: three in the dH pass (measured 2 % faster at d = 256), two elsewhere (in the dE
+            // pass the third costs spilled registers and 7 %)
+            constexpr int RD = (DS == 1 && MODE == MODE_DH) ? 3 : 2;
             constexpr int NB_S = KK / BS;         // batches of the score product
             constexpr int NB_P = 2 * MBH / BS;    // batches of the second product
             static_assert(KK % BS == 0 && MBH % BS == 0, "whole operand batches");
@@ -752,7 +755,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             for (int sb = 0; sb < NSB; ++sb) {
                 f32x16 sv[XG];
                 gp_t gp;
-                uint4 ob[2][BS];
+                uint4 ob[RD][BS];
                 const uint16_t *arow = tile + sb * 32 * D;
                 auto read_batch = [&](int b, uint4 (&dst)[BS]) {
 #pragma unroll
@@ -765,8 +768,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 for (int g = 0; g < XG; ++g)
 #pragma unroll
                     for (int q = 0; q < 16; ++q) sv[g][q] = 0.f;
-                read_batch(0, ob[0]);
-                if (NB_S > 1) read_batch(1, ob[1]);
+#pragma unroll
+                for (int b = 0; b < RD && b < NB_S; ++b) read_batch(b, ob[b]);
 #pragma unroll
                 for (int b = 0; b < NB_S; ++b) {
                     __builtin_amdgcn_sched_barrier(0);
@@ -774,13 +777,13 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     for (int i = 0; i < BS; ++i)
 #pragma unroll
                         for (int g = 0; g < XG; ++g)
-                            sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ob[b & 1][i]), as_bf16x8(xr[g][b * BS + i]), sv[g], 0, 0, 0);
+                            sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ob[b % RD][i]), as_bf16x8(xr[g][b * BS + i]), sv[g], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (b + 2 < NB_S) read_batch(b + 2, ob[b & 1]);
+                    if (b + RD < NB_S) read_batch(b + RD, ob[b % RD]);
                 }
                 if (BWD) {
                     // transpose reads of the first two batches go out before the softmax arithmetic and land under it
-                    s16x8 tb[2][BS];
+                    s16x8 tb[RD][BS];
                     auto read_tr_batch = [&](int b, s16x8 (&dst)[BS]) {
                         const int k2 = b / (MBH / BS);
                         const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D + half * (MBH * 32);
@@ -799,8 +802,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                         if (!kept) continue;
                     }
                     __builtin_amdgcn_sched_barrier(0);
-                    read_tr_batch(0, tb[0]);
-                    read_tr_batch(1, tb[1]);
+#pragma unroll
+                    for (int b = 0; b < RD && b < NB_P; ++b) read_tr_batch(b, tb[b]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (!FILTER) softmax(tile, sb, sv, gp, rows_here, ragged_tag, kept, max_tag);
 #pragma unroll
@@ -811,7 +814,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                         for (int i = 0; i < BS; ++i) {
                             const int mb = (b % (MBH / BS)) * BS + i;
                             bf16x8 av;
-                            __builtin_memcpy(&av, &tb[b & 1][i], 16);
+                            __builtin_memcpy(&av, &tb[b % RD][i], 16);
 #pragma unroll
                             for (int g = 0; g < XG; ++g) {
                                 const uint4 bv = make_uint4(gp[g][k2 * 4 + 0], gp[g][k2 * 4 + 1], gp[g][k2 * 4 + 2], gp[g][k2 * 4 + 3]);
@@ -819,7 +822,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                             }
                         }
                         __builtin_amdgcn_sched_barrier(0);
-                        if (b + 2 < NB_P) read_tr_batch(b + 2, tb[b & 1]);
+                        if (b + RD < NB_P) read_tr_batch(b + RD, tb[b % RD]);
                     }
                 } else {
                     bool kept = true;
