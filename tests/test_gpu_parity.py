@@ -465,3 +465,50 @@ def test_scores_that_outgrow_the_running_maximum_by_hundreds_of_nats(d, mode):
     ref = O.run_workload(w, g=w.g.astype(np.float64))
     assert np.abs(ref.lse).max() > 300
     check_against_oracle(w, out, TOL_BF16)
+
+
+@pytest.mark.parametrize("seed", range(72))
+def test_random_small_shapes_every_mode(seed):
+    """Seeded random draws of shape, mode, dtype, padding, collision flag, algorithm, dH dtype and the reuse flag."""
+    import paper_2509_09682_amd as P
+
+    rng = np.random.default_rng(9000 + seed)
+    mode = [NEG_SHARED, NEG_PER_POSITION, NEG_FULL][seed % 3]
+    dtype = "bf16" if rng.random() < 0.7 else "f32"
+    d = int(rng.choice([64, 128, 256])) if (dtype == "bf16" and rng.random() < 0.7) else int(8 * rng.integers(1, 41))
+    batch, seq = int(rng.integers(1, 9)), int(rng.integers(1, 90))
+    V = int(rng.integers(40, 2500))
+    K = 0 if mode == NEG_FULL else int(rng.integers(1, 400))
+    pad = ["none", "bernoulli", "right"][int(rng.integers(0, 3))]
+    w = make_workload(f"rand{seed}", batch, seq, d, V, K, dtype, mode, 5000 + seed, g_kind="random", pad=pad, pad_p=0.3,
+                      pad_len_lo=0, tgt_dist="zipf" if rng.random() < 0.5 else "uniform", e_sigma=0.2,
+                      mask_collisions=int(rng.integers(0, 2)))
+    tile_ok = dtype == "bf16" and mode != NEG_PER_POSITION and d in (64, 128, 256)
+    algo = P.CCE_ALGO_AUTO if (tile_ok and rng.random() < 0.7) else P.CCE_ALGO_GATHER
+    on_tiles = tile_ok and algo == P.CCE_ALGO_AUTO
+    dH_dtype = P.CCE_BF16 if (dtype == "bf16" and rng.random() < 0.4) else P.CCE_F32
+    reuse = bool(rng.integers(0, 2))
+    print(dict(mode=mode, dtype=dtype, d=d, N=w.N, V=V, K=K, pad=pad, collide=w.mask_collisions, tiles=on_tiles,
+               dH_bf16=dH_dtype == P.CCE_BF16, reuse=reuse))
+    out = _run(w, algo=algo, dH_dtype=dH_dtype, reuse_prep=reuse, use_mask=True)
+    tol = TOL_BF16 if on_tiles else (TOL_F32 if dtype == "f32" else 2e-5)
+    check_against_oracle(w, out, tol, dH_tol=max(tol, 8e-3) if dH_dtype == P.CCE_BF16 else None)
+
+
+@pytest.mark.parametrize("seed", range(18))
+def test_random_medium_shapes_on_the_matrix_core_path(seed):
+    """Several tiles, ragged tails, split and unsplit grids: bf16, shared negatives or full catalogue, d in {64,128,256}."""
+    import paper_2509_09682_amd as P
+
+    rng = np.random.default_rng(7000 + seed)
+    mode = NEG_SHARED if seed % 2 == 0 else NEG_FULL
+    d = [64, 128, 256][seed % 3]
+    batch, seq = int(rng.integers(2, 40)), int(rng.integers(20, 160))
+    V = int(rng.integers(600, 9000))
+    K = 0 if mode == NEG_FULL else int(rng.integers(100, 1600))
+    pad = ["none", "bernoulli", "right"][int(rng.integers(0, 3))]
+    w = make_workload(f"med{seed}", batch, seq, d, V, K, "bf16", mode, 8000 + seed, g_kind="random", pad=pad, pad_p=0.2,
+                      pad_len_lo=seq // 2, tgt_dist="zipf", e_sigma=0.1, mask_collisions=int(rng.integers(0, 2)))
+    reuse = bool(rng.integers(0, 2))
+    print(dict(mode=mode, d=d, N=w.N, V=V, K=K, pad=pad, collide=w.mask_collisions, reuse=reuse))
+    check_against_oracle(w, _run(w, algo=P.CCE_ALGO_TILE, reuse_prep=reuse), TOL_BF16)
