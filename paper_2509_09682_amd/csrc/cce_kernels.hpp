@@ -50,6 +50,7 @@ struct TileArgs {
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
     int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
     float filter_log2;           // backward, gradient filtering: log2 of the threshold; -inf = off
+    int32_t scatter_apart;       // dE launch: 1 = the correct-item scatter has been launched on its own, no leading blocks here
     int32_t tail_slots;          // dH pass, > 0: blocks the chip holds at once; the position blocks of the last, partly filled
                                  // round split the candidate range among the idle block slots (planned on the device from
                                  // the count of valid positions), partial rows in part_dH, summed by the tail merge

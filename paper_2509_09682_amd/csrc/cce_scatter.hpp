@@ -62,7 +62,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
         if (cur != 0xffffffffu) {
 #pragma unroll
             for (int t = 0; t < CPL; ++t) {
-                unsafeAtomicAdd(a.dE + (int64_t)cur * D + lane * CPL + t, accv[t]);
+                unsafeAtomicAdd(a.dE + (int64_t)cur * D + t * 64 + lane, accv[t]);  // an instruction covers 64 consecutive floats
                 accv[t] = 0.f;
             }
         }
@@ -82,7 +82,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
             for (int t = 0; t < CPL; ++t) hv[u][t] = 0.f;
             if (id[u] != 0xffffffffu) {
 #pragma unroll
-                for (int t = 0; t < CPL; ++t) hv[u][t] = load1(a.H + (int64_t)row * D + lane * CPL + t);
+                for (int t = 0; t < CPL; ++t) hv[u][t] = load1(a.H + (int64_t)row * D + t * 64 + lane);
             }
         }
 #pragma unroll

@@ -1420,7 +1420,7 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
     if (fine && a.splits > 1) a.splits = max_splits;
     int64_t blocks = xblocks * a.splits;
     if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
-        a.pos_blocks = (a.N + kPosChunk - 1) / kPosChunk;
+        a.pos_blocks = a.scatter_apart ? 0 : (a.N + kPosChunk - 1) / kPosChunk;
         blocks += a.pos_blocks;
     }
     if (MODE == MODE_DH) {
@@ -1540,6 +1540,13 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         return e;
     }
     case TILE_PASS_DE:
+        if constexpr (D > 128) {
+            // One block of eight wavefronts per compute unit: scatter blocks at the head of this launch would run 256
+            // at a time, one long latency chain each, before any tile block starts (c5: 330 us of a 970 us launch).
+            // On their own they run many to a compute unit.
+            a.scatter_apart = 1;
+            if ((e = launch_pos_scatter(a, stream)) != hipSuccess) return e;
+        }
         if constexpr (XG_B == 2) {
             if (wide(a.n_cols, false)) return launch_tile_kernel<D, MODE_DE, BY_B, 4, 2, MINB, NBUF_B>(a, a.n_cols, stream);
         }
