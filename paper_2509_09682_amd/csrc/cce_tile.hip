@@ -1393,6 +1393,9 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_me
         const int64_t blocks = xblocks * s;
         const int64_t rounds = (blocks + slots - 1) / slots;
         const double eff = (double)blocks / (double)(rounds * slots);
+        // forward pass: the block count is an upper bound when positions are padded, and every split repeats the
+        // block prologue: the first factor that fills the last round reasonably is taken (c5: 2 instead of 4, 394 -> 361 us)
+        if (cheap_merge && eff >= 0.88) return s;
         if (eff > best_eff * 1.05) {
             best_eff = eff;
             best = s;
