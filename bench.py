@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the CCE- hot path on one MI355X: forward + backward of the loss over one synthetic batch.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--algo auto|gather|tile]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--algo auto|gather|tile]
 
 A step is one cce_neg_forward followed by one cce_neg_backward on inputs already resident in HBM.  The line printed on
-stdout is one JSON object: whole-job positions/s, the roofline of the dominant kernel (timed with events on the launch
-stream inside the timed region), and the fp64 CPU oracle timed on a bounded sample of the same workload.
+stdout is one JSON object: whole-job positions/s of the headline workload (the largest single-GPU one, c5, unless
+--config names another), the roofline of its dominant kernel (timed with events on the launch stream), the fp64 CPU
+oracle timed on a bounded sample of the same workload, and, under "other_workloads", the same step measured on the
+remaining workloads (c1: microseconds only; c2-c4: step time, positions/s, dominant kernel and its roofline fraction).
 """
 from __future__ import annotations
 
@@ -18,7 +20,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 EXP_PER_S = 12.5e12           # measured v_exp_f32 rate of the whole chip (profiles/microbenchmarks.md)
@@ -112,18 +113,180 @@ def measured_traffic(workload, family):
     return None
 
 
+def measure(w, args, *, headline: bool) -> dict:
+    """K timed steps of forward + backward on workload w, then the per-kernel breakdown.  Returns the result fields."""
+    import numpy as np
+    import torch
+
+    import paper_2509_09682_amd as P
+    from paper_2509_09682_amd.runner import to_device
+
+    steps, warmup = (args.steps, args.warmup) if headline else (args.other_steps, args.warmup)
+    H, E, tgt, neg, mask = to_device(w)
+    algo = {"auto": P.CCE_ALGO_AUTO, "gather": P.CCE_ALGO_GATHER, "tile": P.CCE_ALGO_TILE}[args.algo]
+    in_dt = P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16
+    filter_eps = args.filter_eps if headline else 0.0
+    desc = P.make_desc(w.N, w.V, w.d, w.K, in_dt, w.neg_mode, mask_target_collisions=w.mask_collisions,
+                       validate_indices=0, algo=algo)
+    # a training step runs the backward pass right after the forward pass of the same batch on the same workspace:
+    # the backward call may then reuse what the forward call left there
+    desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, in_dt, w.neg_mode, mask_target_collisions=w.mask_collisions,
+                           validate_indices=0, algo=algo, reuse_forward_prep=0 if args.no_reuse_prep else 1,
+                           filter_eps=filter_eps)
+    ws = P.new_workspace(desc)
+    loss = torch.empty(w.N, device="cuda")
+    lse = torch.empty(w.N, device="cuda")
+    g = torch.from_numpy(w.g).cuda()
+    dH = torch.empty((w.N, w.d), device="cuda")
+    dE = torch.zeros((w.V, w.d), device="cuda")
+
+    smp = None
+    sampler = args.sampler if headline else "none"
+    if sampler != "none":
+        from paper_2509_09682_amd.runner import device_sampler
+        from workloads import alias_table, popularity_weights
+        table = ()
+        if sampler == "alias":   # the popularity law of workload c5 over a seeded rank -> id permutation
+            table = alias_table(popularity_weights(np.random.default_rng(3).permutation(w.V).astype(np.int32), 1.2, 0.75))
+        smp, smp_keep = device_sampler(P.CCE_SAMPLER_UNIFORM if sampler == "uniform" else P.CCE_SAMPLER_ALIAS,
+                                       w.notes["seed"], 0, *table)
+        neg = None
+        step_no = [0]
+
+    def forward():
+        if smp is None:
+            return P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
+        step_no[0] += 1
+        smp.stream = step_no[0] & 0xFFFFFFFF     # other negatives every step; the backward call repeats the number
+        return P.cce_neg_forward_sampled(desc, smp, H, E, tgt, mask, loss, lse, ws)
+
+    def backward():
+        if smp is None:
+            return P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
+        return P.cce_neg_backward_sampled(desc_bwd, smp, H, E, tgt, mask, lse, g, dH, dE, ws)
+
+    def step():
+        forward()
+        backward()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps bracketed by synchronisation, nothing else on the stream.  Peak memory of the
+    # region: everything the step needs (inputs, outputs, workspace) is allocated by now and the steps allocate nothing.
+    torch.cuda.reset_peak_memory_stats()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / steps
+    peak_allocated = int(torch.cuda.max_memory_allocated())
+    free_b, total_b = torch.cuda.mem_get_info()          # hipMemGetInfo: the device's own view, allocator caches and
+    device_in_use = int(total_b - free_b)                # the runtime's context included
+
+    # forward / backward split of the same steps (events on the launch stream), outside the timed region
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for k in range(steps):
+        ev[k][0].record()
+        forward()
+        ev[k][1].record()
+        backward()
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    # cold caches: a 1 GiB write between steps evicts L2 and the Infinity Cache
+    cold_ms = None
+    if headline and args.cold_reps > 0:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        c = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.cold_reps)]
+        for k in range(args.cold_reps):
+            scratch.fill_(float(k))
+            c[k][0].record()
+            step()
+            c[k][1].record()
+        torch.cuda.synchronize()
+        cold_ms = float(np.median([e[0].elapsed_time(e[1]) for e in c]))
+        del scratch
+
+    # dE zero-fill, reported apart from the step (dE is an accumulate-into buffer owned by the caller)
+    z0, z1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    z0.record()
+    dE.zero_()
+    z1.record()
+    torch.cuda.synchronize()
+    memset_ms = z0.elapsed_time(z1)
+
+    # per-kernel durations: the same K steps once more with the library's event brackets switched on
+    P.cce_neg_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    fam = P.cce_neg_profile_read()
+    P.cce_neg_profile_enable(False)
+    kernels = {k: {"avg_ms": ms / n, "launches_per_step": n / steps} for k, (ms, n) in fam.items()}
+    dominant = max(fam, key=lambda k: fam[k][0])
+    dom_ms = fam[dominant][0] / fam[dominant][1]
+
+    flops, bytes_min = algorithmic_work(w)
+    bound, work = kernel_work(w, dominant)
+    if bound == "mfma":
+        peak = PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS
+        roof = {"bound": "mfma", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": peak,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = measured_traffic(w.name, dominant)
+    roof["avg_launch_ms"] = dom_ms
+    roof["algorithmic_per_launch"] = work
+
+    mfma_bound = w.in_dtype == "bf16" and w.neg_mode != 1
+    whole = {"tflops": flops / (ms_step * 1e-3) / 1e12, "frac_mfma_peak": flops / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+             "gbytes_per_s": bytes_min / (ms_step * 1e-3) / 1e9, "frac_hbm_peak": bytes_min / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+             "bound": "mfma" if mfma_bound else "hbm"}
+    whole["frac"] = whole["frac_mfma_peak"] if mfma_bound else whole["frac_hbm_peak"]
+    config = {
+        "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
+        "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
+        "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": filter_eps, "sampler": sampler,
+        "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
+        "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
+        "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,
+        "algorithmic_gflop": flops / 1e9, "algorithmic_mbytes": bytes_min / 1e6,
+        "whole_step": whole,
+        "hbm_bytes": {"inputs": int(H.numel() * H.element_size() + E.numel() * E.element_size() + tgt.numel() * 4
+                                    + (0 if neg is None else neg.numel() * 4) + w.N),
+                      "outputs": int(w.N * 8 + dH.numel() * 4 + dE.numel() * 4),
+                      "workspace": int(ws.numel()),
+                      "peak_allocated_in_timed_region": peak_allocated,
+                      "device_in_use_hipMemGetInfo": device_in_use},
+    }
+    return {"ms_per_step": ms_step, "value": w.N / (ms_step * 1e-3), "steps": steps, "config": config, "roofline": roof}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the config the metric is quoted on)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="headline workload 1..5 (default 5: the largest single-GPU workload; the metric names no config)")
+    ap.add_argument("--others", default="auto",
+                    help="comma-separated workloads measured as well and reported under other_workloads "
+                         "(auto: the remaining ones of 1..5 when the headline is the default, none otherwise)")
+    ap.add_argument("--other-steps", type=int, default=30, help="timed steps per workload of --others")
     ap.add_argument("--algo", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold-reps", type=int, default=5, help="steps timed with a 1 GiB cache-evicting write in front (0 = skip)")
     ap.add_argument("--filter-eps", type=float, default=0.0, help="gradient filtering threshold (full-catalogue workload c4 only)")
     ap.add_argument("--peaked", action="store_true", help="hidden states that point at their target row: a concentrated softmax, as late in training (c4)")
-    ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes the padding compaction of the forward call")
+    ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes what the forward call left in the workspace")
     ap.add_argument("--sampler", default="none", choices=["none", "uniform", "alias"],
                     help="draw the negatives inside the kernels (shared / per-position workloads): no index array is read")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")
@@ -151,8 +314,6 @@ def main() -> int:
         print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 5}))
         return 0
 
-    import paper_2509_09682_amd as P
-    from hip_harness import to_device
     from workloads import config
 
     w = config(args.config)
@@ -163,152 +324,23 @@ def main() -> int:
         scale = 9.0 / float(np.mean(np.sum(Ef * Ef, axis=1)))   # correct-item score about 9 above the rest
         w.H = bf16_bits_from_f32((scale * Ef[w.tgt] + 0.5 * rng.standard_normal((w.N, w.d)).astype(np.float32)).astype(np.float32))
         w.name += "_peaked"
-    H, E, tgt, neg, mask = to_device(w)
-    algo = {"auto": P.CCE_ALGO_AUTO, "gather": P.CCE_ALGO_GATHER, "tile": P.CCE_ALGO_TILE}[args.algo]
-    desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
-                       mask_target_collisions=w.mask_collisions, validate_indices=0, algo=algo)
-    # a training step runs the backward pass right after the forward pass of the same batch on the same workspace:
-    # the backward call may then reuse the forward call's compaction of the padded positions
-    desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
-                           mask_target_collisions=w.mask_collisions, validate_indices=0, algo=algo,
-                           reuse_forward_prep=0 if args.no_reuse_prep else 1, filter_eps=args.filter_eps)
-    ws = P.new_workspace(desc)
-    loss = torch.empty(w.N, device="cuda")
-    lse = torch.empty(w.N, device="cuda")
-    g = torch.from_numpy(w.g).cuda()
-    dH = torch.empty((w.N, w.d), device="cuda")
-    dE = torch.zeros((w.V, w.d), device="cuda")
-
-    smp = None
-    if args.sampler != "none":
-        from hip_harness import device_sampler
-        from workloads import alias_table, popularity_weights
-        table = ()
-        if args.sampler == "alias":   # the popularity law of workload c5 over a seeded rank -> id permutation
-            table = alias_table(popularity_weights(np.random.default_rng(3).permutation(w.V).astype(np.int32), 1.2, 0.75))
-        smp, smp_keep = device_sampler(P.CCE_SAMPLER_UNIFORM if args.sampler == "uniform" else P.CCE_SAMPLER_ALIAS,
-                                       w.notes["seed"], 0, *table)
-        neg = None
-        step_no = [0]
-
-    def forward():
-        if smp is None:
-            return P.cce_neg_forward(desc, H, E, tgt, neg, mask, loss, lse, ws)
-        step_no[0] += 1
-        smp.stream = step_no[0] & 0xFFFFFFFF     # other negatives every step; the backward call repeats the number
-        return P.cce_neg_forward_sampled(desc, smp, H, E, tgt, mask, loss, lse, ws)
-
-    def backward():
-        if smp is None:
-            return P.cce_neg_backward(desc_bwd, H, E, tgt, neg, mask, lse, g, dH, dE, ws)
-        return P.cce_neg_backward_sampled(desc_bwd, smp, H, E, tgt, mask, lse, g, dH, dE, ws)
-
-    def step():
-        forward()
-        backward()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # timed region: exactly K steps bracketed by synchronisation, nothing else on the stream
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_step = (t1 - t0) * 1e3 / args.steps
-
-    # forward / backward split of the same steps (events on the launch stream), outside the timed region
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for k in range(args.steps):
-        ev[k][0].record()
-        forward()
-        ev[k][1].record()
-        backward()
-        ev[k][2].record()
-    torch.cuda.synchronize()
-    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-
-    # cold caches: a 1 GiB write between steps evicts L2 and the Infinity Cache
-    cold_ms = None
-    if args.cold_reps > 0:
-        scratch = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
-        c = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.cold_reps)]
-        for k in range(args.cold_reps):
-            scratch.fill_(float(k))
-            c[k][0].record()
-            step()
-            c[k][1].record()
-        torch.cuda.synchronize()
-        cold_ms = float(np.median([e[0].elapsed_time(e[1]) for e in c]))
-        del scratch
-
-    # dE zero-fill, reported apart from the step (dE is an accumulate-into buffer owned by the caller)
-    z0, z1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    z0.record()
-    dE.zero_()
-    z1.record()
-    torch.cuda.synchronize()
-    memset_ms = z0.elapsed_time(z1)
-
-    # per-kernel durations: the same K steps once more with the library's event brackets switched on
-    P.cce_neg_profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    fam = P.cce_neg_profile_read()
-    P.cce_neg_profile_enable(False)
-    kernels = {k: {"avg_ms": ms / n, "launches_per_step": n / args.steps} for k, (ms, n) in fam.items()}
-    dominant = max(fam, key=lambda k: fam[k][0])
-    dom_ms = fam[dominant][0] / fam[dominant][1]
-
-    flops, bytes_min = algorithmic_work(w)
-    bound, work = kernel_work(w, dominant)
-    if bound == "mfma":
-        peak = PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS
-        roof = {"bound": "mfma", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": peak,
-                "unit": "TFLOP/s"}
-    else:
-        roof = {"bound": "hbm", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                "unit": "GB/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = measured_traffic(w.name, dominant)
-    roof["avg_launch_ms"] = dom_ms
-    roof["algorithmic_per_launch"] = work
+    res = measure(w, args, headline=True)
 
     out = {
         "metric": "CE- fwd+bwd positions/sec at 1 GPU",
-        "value": w.N / (ms_step * 1e-3),
+        "value": res["value"],
         "unit": "positions/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_step,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16" if w.in_dtype == "bf16" else "f32",
         "data": "synthetic",
-        "config": {
-            "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
-            "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
-            "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": args.filter_eps, "sampler": args.sampler,
-            "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
-            "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
-            "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,
-            "algorithmic_gflop": flops / 1e9, "algorithmic_mbytes": bytes_min / 1e6,
-            "whole_step_tflops": flops / (ms_step * 1e-3) / 1e12,
-            "whole_step_frac_mfma_peak": flops / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
-            "hbm_bytes": {"inputs": int(H.numel() * H.element_size() + E.numel() * E.element_size() + tgt.numel() * 4
-                                        + (0 if neg is None else neg.numel() * 4) + w.N),
-                          "outputs": int(w.N * 8 + dH.numel() * 4 + dE.numel() * 4),
-                          "workspace": int(ws.numel()),
-                          "torch_peak_allocated": int(torch.cuda.max_memory_allocated())},
-        },
-        "roofline": roof,
+        "config": res["config"],
+        "roofline": res["roofline"],
     }
 
     if not args.no_cpu_baseline:
@@ -329,6 +361,33 @@ def main() -> int:
             "value": (n_sample / dt) * (w.N / max(w.n_valid, 1)), "unit": "positions/s", "cores": O.num_threads(),
             "kind": "oracle", "sample": f"first {n_sample} valid positions of {w.name} (fwd+bwd, fp64, {dt:.1f} s)",
         }
+
+    # the remaining workloads, one after the other on the same GPU (inputs of the previous one are released first)
+    if args.others == "auto":
+        others = [i for i in (1, 2, 3, 4, 5) if i != args.config] if (args.config == 5 and not args.peaked) else []
+    else:
+        others = [int(x) for x in args.others.split(",") if x.strip()]
+    del w
+    out["other_workloads"] = []
+    for idx in others:
+        torch.cuda.empty_cache()
+        wo = config(idx)
+        r = measure(wo, args, headline=False)
+        c, roof = r["config"], r["roofline"]
+        entry = {"workload": wo.name, "ms_per_step": r["ms_per_step"], "us_per_step": r["ms_per_step"] * 1e3,
+                 "steps": r["steps"]}
+        if idx != 1:   # c1 is a correctness workload (30 MFLOP): latency only, no roofline claim
+            entry.update({
+                "positions_per_s": r["value"], "valid_positions_per_s": c["valid_positions_per_s"],
+                "dominant_kernel": roof["kernel"], "bound": roof["bound"], "frac": roof["frac"],
+                "achieved": roof["achieved"], "unit": roof["unit"], "traffic": roof["traffic"],
+                "whole_step_bound": c["whole_step"]["bound"], "whole_step_frac": c["whole_step"]["frac"],
+                "fwd_ms": c["fwd_ms"], "bwd_ms": c["bwd_ms"], "dE_zero_fill_ms": c["dE_zero_fill_ms"],
+                "kernels": {k: round(v["avg_ms"], 5) for k, v in c["kernels"].items()},
+                "peak_allocated_in_timed_region": c["hbm_bytes"]["peak_allocated_in_timed_region"],
+            })
+        out["other_workloads"].append(entry)
+        del wo
 
     print(json.dumps(out))
     return 0

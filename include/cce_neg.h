@@ -68,7 +68,8 @@ typedef struct {
     int32_t dH_dtype;               /* cce_dtype of dH: F32, or BF16 (round-to-nearest-even) when in_dtype is BF16 */
     int32_t neg_mode;               /* cce_neg_mode */
     int32_t mask_target_collisions; /* 1: a negative equal to the position's own target is left out of LSE and gradients */
-    int32_t validate_indices;       /* 1: kernels range-check ids of valid positions, skip bad ones and raise the status word */
+    int32_t validate_indices;       /* 1: kernels range-check ids of valid positions, never dereference bad ones and raise the
+                                       status word (see cce_neg_index_status for what a flagged call returns) */
     int32_t algo;                   /* cce_algo */
     int32_t reuse_forward_prep;     /* backward only, 1: the caller vouches that the workspace still holds what the
                                        forward call with this descriptor and the same tgt / neg / mask contents left
@@ -81,7 +82,8 @@ typedef struct {
                                        assumption.  With 1 and a workspace that does not hold them the results are
                                        undefined. */
     float filter_eps;               /* backward only, gradient filtering of the full-catalogue mode (Sec. 3.1, last
-                                       paragraph; Sec. 4.3): 0 = off.  > 0: the softmax matrix of the valid positions
+                                       paragraph; threshold sweep: Sec. 5, "Gradient Filtering with CCE", and the
+                                       appendix "Sparsity Threshold Analysis"): 0 = off.  > 0: the softmax matrix of the valid positions
                                        (batch order) by the items (id order) is cut into 32 x 32 blocks aligned at the
                                        origin, and a block whose largest probability is below filter_eps counts as
                                        zero in Eq. 6 (it adds nothing to dH or dE; the term of the correct item stays).
@@ -185,8 +187,11 @@ cce_status cce_neg_backward_sampled(const cce_desc *desc, const cce_sampler *sam
 /*
  * Synchronises hip_stream and reads the index status word kept in workspace.  Returns CCE_ERR_INDEX if any call on
  * that workspace since the last query found an id outside [0,V) on a valid position (validate_indices = 1 only),
- * CCE_OK otherwise; the word is cleared.  Bad ids are never dereferenced: a bad negative is skipped, a position with a
- * bad target is treated as padding.
+ * CCE_OK otherwise; the word is cleared.  Bad ids are never dereferenced.  Row-gather kernels (per-position mode, fp32
+ * inputs, CCE_ALGO_GATHER): a bad negative is skipped and a position with a bad target is treated as padding, so the
+ * outputs are those of the sanitised problem.  Matrix-core kernels (bf16 shared / full mode): a position with a bad
+ * target is treated as padding, but a bad SHARED negative is scored as item 0 in its place; the outputs of a flagged
+ * call are then unspecified (finite, in bounds, and dE row 0 may have received gradient): discard them.
  */
 cce_status cce_neg_index_status(void *workspace, size_t workspace_bytes, void *hip_stream);
 

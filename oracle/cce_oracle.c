@@ -39,7 +39,8 @@
  *
  * Gradient filtering (Sec. 3.1, last paragraph: computations with values below a
  * prescribed threshold are disregarded in the backward pass; Sec. 3.3 notes that it
- * can follow step 4 of Alg. 2; Sec. 4.3 sweeps the threshold filter_eps).  The paper
+ * can follow step 4 of Alg. 2; Sec. 5, "Gradient Filtering with CCE", and the appendix
+ * "Sparsity Threshold Analysis" sweep the threshold filter_eps).  The paper
  * gives no granularity.  Reading taken here: the softmax matrix of the valid
  * positions (batch order) by the candidates (catalogue order) is cut into square
  * blocks of `block` entries a side, aligned at the origin; a block whose largest
@@ -50,7 +51,8 @@
  * Parity pins: the tests under tests/ (marker "not gpu") check this file against
  * brute-force full softmax, the K = V-1 full-catalogue identity, central finite
  * differences, closed forms (H = 0, dominant score), softmax rows summing to 1,
- * the zero column sum of dE, a literal transcription of Alg. 1 / Alg. 2, and
+ * the zero column sum of dE, random partitions of the candidates merged pairwise (the
+ * identity behind Alg. 1), sparse matrix products for Eq. 6, and
  * torch's fp64 logsumexp / autograd on explicitly gathered logits.
  */
 #include <math.h>

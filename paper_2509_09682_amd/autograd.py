@@ -41,6 +41,7 @@ class _CceNegLoss(torch.autograd.Function):
         dt = B.CCE_F32 if H.dtype == torch.float32 else B.CCE_BF16
         kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0)
         desc = B.make_desc(N, V, d, K, dt, neg_mode, **kw)
+        B.check_step_args(desc, H, E, tgt, neg, mask, sampled=sampler is not None)   # before anything touches the device
         global _serial
         key, ws = _workspace(desc, H.device)
         _serial += 1

@@ -112,6 +112,48 @@ def _ptr(t: Optional[torch.Tensor]):
     return ctypes.c_void_p(t.data_ptr())
 
 
+_BF16_CARRIERS = (torch.bfloat16, torch.int16, torch.uint16)   # bf16 values, or their bit patterns in a 16-bit integer tensor
+
+
+def _want(name: str, t: Optional[torch.Tensor], dtypes, numel: int, *, optional: bool = False) -> None:
+    """Raises before any launch unless tensor `name` has one of `dtypes` and exactly `numel` elements."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if t.dtype not in dtypes:
+        raise TypeError(f"{name} must have dtype {' or '.join(str(x) for x in dtypes)}, got {t.dtype} "
+                        "(the kernels read the raw bytes: no conversion happens at this boundary)")
+    if t.numel() != numel:
+        raise ValueError(f"{name} must hold {numel} elements for this descriptor, got {tuple(t.shape)}")
+
+
+def check_step_args(desc: CceDesc, H, E, tgt, neg, mask, *, sampled: bool = False, loss=None, lse=None, grad_loss=None,
+                    dH=None, dE=None) -> None:
+    """Dtype and size checks of the tensors of a forward or backward call against the descriptor.
+
+    The C ABI takes plain pointers and trusts the sizes in the descriptor, so a torch.long index tensor, a short mask
+    or a per-position `neg` of another shape would be read as garbage or out of bounds; they are refused here.
+    """
+    if desc.neg_mode not in (CCE_NEG_SHARED, CCE_NEG_PER_POSITION, CCE_NEG_FULL):
+        raise ValueError(f"unknown neg_mode {desc.neg_mode}")
+    elem = (torch.float32,) if desc.in_dtype == CCE_F32 else _BF16_CARRIERS
+    N, V, d, K = int(desc.N), int(desc.V), int(desc.d), int(desc.K)
+    _want("H", H, elem, N * d)
+    _want("E", E, elem, V * d)
+    _want("tgt", tgt, (torch.int32,), N)
+    if not sampled and desc.neg_mode != CCE_NEG_FULL and K > 0:
+        _want("neg", neg, (torch.int32,), K if desc.neg_mode == CCE_NEG_SHARED else N * K)
+        if desc.neg_mode == CCE_NEG_PER_POSITION and neg.dim() == 2 and tuple(neg.shape) != (N, K):
+            raise ValueError(f"per-position neg must be [N, K] = [{N}, {K}], got {tuple(neg.shape)}")
+    _want("mask", mask, (torch.uint8, torch.bool), N, optional=True)
+    _want("loss", loss, (torch.float32,), N, optional=True)
+    _want("lse", lse, (torch.float32,), N, optional=True)
+    _want("grad_loss", grad_loss, (torch.float32,), N, optional=True)
+    _want("dH", dH, (torch.float32,) if desc.dH_dtype == CCE_F32 else _BF16_CARRIERS, N * d, optional=True)
+    _want("dE", dE, (torch.float32,), V * d, optional=True)
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -136,6 +178,7 @@ def new_workspace(desc: CceDesc, device="cuda") -> torch.Tensor:
 
 
 def cce_neg_forward(desc: CceDesc, H, E, tgt, neg, mask, loss, lse, workspace, *, check: bool = True) -> int:
+    check_step_args(desc, H, E, tgt, neg, mask, loss=loss, lse=lse)
     st = lib().cce_neg_forward(ctypes.byref(desc), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg), _ptr(mask), _ptr(loss),
                                _ptr(lse), _ptr(workspace),
                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
@@ -145,6 +188,7 @@ def cce_neg_forward(desc: CceDesc, H, E, tgt, neg, mask, loss, lse, workspace, *
 
 
 def cce_neg_backward(desc: CceDesc, H, E, tgt, neg, mask, lse, grad_loss, dH, dE, workspace, *, check: bool = True) -> int:
+    check_step_args(desc, H, E, tgt, neg, mask, lse=lse, grad_loss=grad_loss, dH=dH, dE=dE)
     st = lib().cce_neg_backward(ctypes.byref(desc), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg), _ptr(mask), _ptr(lse),
                                 _ptr(grad_loss), _ptr(dH), _ptr(dE), _ptr(workspace),
                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
@@ -174,6 +218,7 @@ def cce_neg_sample(desc: CceDesc, sampler: CceSampler, neg_out, *, check: bool =
 
 def cce_neg_forward_sampled(desc: CceDesc, sampler: CceSampler, H, E, tgt, mask, loss, lse, workspace, *,
                             check: bool = True) -> int:
+    check_step_args(desc, H, E, tgt, None, mask, sampled=True, loss=loss, lse=lse)
     st = lib().cce_neg_forward_sampled(ctypes.byref(desc), ctypes.byref(sampler), _ptr(H), _ptr(E), _ptr(tgt), _ptr(mask),
                                        _ptr(loss), _ptr(lse), _ptr(workspace),
                                        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
@@ -184,6 +229,7 @@ def cce_neg_forward_sampled(desc: CceDesc, sampler: CceSampler, H, E, tgt, mask,
 
 def cce_neg_backward_sampled(desc: CceDesc, sampler: CceSampler, H, E, tgt, mask, lse, grad_loss, dH, dE, workspace, *,
                              check: bool = True) -> int:
+    check_step_args(desc, H, E, tgt, None, mask, sampled=True, lse=lse, grad_loss=grad_loss, dH=dH, dE=dE)
     st = lib().cce_neg_backward_sampled(ctypes.byref(desc), ctypes.byref(sampler), _ptr(H), _ptr(E), _ptr(tgt), _ptr(mask),
                                         _ptr(lse), _ptr(grad_loss), _ptr(dH), _ptr(dE), _ptr(workspace),
                                         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())

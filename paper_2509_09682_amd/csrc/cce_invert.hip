@@ -97,6 +97,8 @@ hipError_t launch_scan(int32_t *data, int64_t n, int32_t *block_sums, hipStream_
     const unsigned blocks = (unsigned)((n + kScanChunk - 1) / kScanChunk);
     if (blocks == 0) return hipSuccess;
     hipLaunchKernelGGL(scan_local_kernel, dim3(blocks), dim3(kScanThreads), 0, stream, data, n, block_sums);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(scan_add_kernel, dim3(blocks), dim3(kScanThreads), 0, stream, data, n, block_sums);
     return hipGetLastError();
 }

@@ -19,6 +19,8 @@
 // target: the dense tile counts those c_i copies, the definition wants the target exactly once, so
 //   sum_live exp(o) = sum_k exp(o_ik) + w_i exp(o+_i),   coefficient of the correct item = g_i (w_i p+_i - 1).
 // With collision masking off w_i = 1; in full-catalogue mode the target is already one of the columns and w_i = 0.
+#include <atomic>
+
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
 #include "cce_scatter.hpp"
@@ -869,7 +871,8 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             }
             process_tile(t, cur, Full{}, Lazy{});
 #pragma unroll
-            for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 3.0e38f);  // overflow (or NaN)
+            for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 1.0e30f);  // near overflow (or NaN): the merges of
+                                                                              // half-waves and of split runs add up to 16 such sums
             if (__any(over)) {
 #pragma unroll
                 for (int g = 0; g < XG; ++g) {
@@ -1368,16 +1371,25 @@ __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------------------------------
-// Blocks of one kernel instantiation that the whole chip holds at once (queried once).
+// Blocks of one kernel instantiation that the current device holds at once.  The answer is cached per instantiation
+// (the template makes the static array one per kernel) and per device ordinal.
+constexpr int kMaxDevices = 64;
 template <typename K>
 int resident_blocks(K kernel, int threads)
 {
-    int per_cu = 0, dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+    static std::atomic<int> cache[kMaxDevices];  // 0 = not asked yet
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    const bool cached = dev >= 0 && dev < kMaxDevices;
+    if (cached) {
+        const int v = cache[dev].load(std::memory_order_relaxed);
+        if (v > 0) return v;
+    }
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1 ||
         hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1)
         return 256;
-    return per_cu * prop.multiProcessorCount;
+    if (cached) cache[dev].store(per_cu * cus, std::memory_order_relaxed);
+    return per_cu * cus;
 }
 
 // Split factor in [1, max_splits] that wastes the least of the last round of blocks; ties go to the smaller factor,
@@ -1436,7 +1448,7 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
 template <int D, int MODE, int BY, int NW, int XG, int MINB, int NBUF, int DS = 1, bool FILTER = false>
 hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
 {
-    static const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>, NW * 64);
+    const int slots = resident_blocks(tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>, NW * 64);
     constexpr int XPB = (NW / DS) * XG * 32;
     int64_t blocks = plan_tile_grid<MODE>(a, n_x, XPB, NW * 64, slots);
     if (blocks == 0) return hipSuccess;
@@ -1454,7 +1466,7 @@ template <int D, int XG_DH, int XG_DE, bool FILTER = false>
 hipError_t launch_bwd_kernel(TileArgs &a_dh, TileArgs &a_de, hipStream_t stream)
 {
     constexpr int BY = 8192 / D, NBUF = 4;
-    static const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>, 256);
+    const int slots = resident_blocks(tile_bwd_kernel<D, BY, XG_DH, XG_DE, NBUF, FILTER>, 256);
     const int64_t de_blocks = plan_tile_grid<MODE_DE>(a_de, a_de.n_cols, 4 * XG_DE * 32, 256, slots);
     const int64_t dh_blocks = plan_tile_grid<MODE_DH>(a_dh, a_dh.N, 4 * XG_DH * 32, 256, slots, true);
     if (de_blocks + dh_blocks == 0) return hipSuccess;
@@ -1572,7 +1584,8 @@ hipError_t launch_bwd_for_d(TileArgs a_dh, TileArgs a_de, hipStream_t stream)
         constexpr int PPB = 256 / (D / 8);
         ProfScope prof(PROF_BWD_PRE, stream);
         hipLaunchKernelGGL((bwd_pre_kernel<D>), dim3((unsigned)((a_dh.N + PPB - 1) / PPB)), dim3(256), 0, stream, a_dh);
-        if (hipGetLastError() != hipSuccess) return hipGetLastError();
+        const hipError_t pre = hipGetLastError();  // reading the error clears it: read it once
+        if (pre != hipSuccess) return pre;
     }
     // two groups of stationary rows per wavefront under the same rule as for the separate launches
     auto wide = [&](int64_t n_x, int splits, bool may_split) {

@@ -125,3 +125,63 @@ def test_sampled_calls_reject_bad_samplers_before_launch(binding):
     a = B.cce_neg_workspace_bytes(B.make_desc(512, 4096, 64, 128, B.CCE_F32, B.CCE_NEG_SHARED))
     b = B.cce_neg_workspace_bytes(B.make_desc(512, 4096, 64, 1024, B.CCE_F32, B.CCE_NEG_SHARED))
     assert b - a >= (1024 - 128) * 4
+
+
+def test_binding_refuses_wrong_dtypes_and_shapes_before_any_launch(binding):
+    """The C ABI reads raw bytes: a torch.long index tensor, a short mask or a mis-shaped per-position `neg` must be
+    refused by the binding (and so by cce_neg_loss) before a pointer is formed.  CPU tensors suffice: a call that got
+    past the checks would stop at the CUDA-tensor requirement, with another message."""
+    import torch
+
+    B = binding
+    N, V, d, K = 6, 50, 16, 4
+    desc = B.make_desc(N, V, d, K, B.CCE_F32, B.CCE_NEG_PER_POSITION)
+    H, E = torch.zeros(N, d), torch.zeros(V, d)
+    tgt = torch.zeros(N, dtype=torch.int32)
+    neg = torch.zeros(N, K, dtype=torch.int32)
+    mask = torch.ones(N, dtype=torch.uint8)
+    loss, lse = torch.zeros(N), torch.zeros(N)
+    ws = torch.zeros(1 << 16, dtype=torch.uint8)
+
+    def fwd(**kw):
+        a = dict(H=H, E=E, tgt=tgt, neg=neg, mask=mask, loss=loss, lse=lse)
+        a.update(kw)
+        return B.cce_neg_forward(desc, a["H"], a["E"], a["tgt"], a["neg"], a["mask"], a["loss"], a["lse"], ws)
+
+    with pytest.raises(TypeError, match="tgt"):
+        fwd(tgt=tgt.long())
+    with pytest.raises(TypeError, match="neg"):
+        fwd(neg=neg.long())
+    with pytest.raises(TypeError, match="mask"):
+        fwd(mask=mask.float())
+    with pytest.raises(TypeError, match="H"):
+        fwd(H=H.double())
+    with pytest.raises(ValueError, match="tgt"):
+        fwd(tgt=tgt[:-1])
+    with pytest.raises(ValueError, match="mask"):
+        fwd(mask=mask[:-1])
+    with pytest.raises(ValueError, match="neg"):
+        fwd(neg=neg[:, :-1])
+    with pytest.raises(ValueError, match="neg"):
+        fwd(neg=neg.t().contiguous())          # [K, N]: right size, wrong shape
+    with pytest.raises(ValueError, match="neg"):
+        fwd(neg=None)
+    with pytest.raises(ValueError, match="E"):
+        fwd(E=E[:-1])
+    with pytest.raises(ValueError, match="CUDA"):   # well-formed arguments get as far as the device-pointer requirement
+        fwd()
+    g, dH, dE = torch.zeros(N), torch.zeros(N, d), torch.zeros(V, d)
+    with pytest.raises(TypeError, match="dE"):
+        B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH, dE.double(), ws)
+    with pytest.raises(TypeError, match="dH"):
+        B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g, dH.bfloat16(), dE, ws)
+    with pytest.raises(ValueError, match="grad_loss"):
+        B.cce_neg_backward(desc, H, E, tgt, neg, mask, lse, g[:-1], dH, dE, ws)
+    bad_mode = B.make_desc(N, V, d, K, B.CCE_F32, 7)
+    with pytest.raises(ValueError, match="neg_mode"):
+        B.cce_neg_forward(bad_mode, H, E, tgt, neg, mask, loss, lse, ws)
+    # the autograd front end goes through the same checks
+    from paper_2509_09682_amd import cce_neg_loss
+
+    with pytest.raises(TypeError, match="tgt"):
+        cce_neg_loss(H, E, tgt.long(), neg, mask, neg_mode=B.CCE_NEG_PER_POSITION)

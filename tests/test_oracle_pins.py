@@ -11,7 +11,6 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import alg_literal
 from oracle import cce_oracle as O
 from workloads import bf16_bits_from_f32, f32_from_bf16_bits
 
@@ -273,24 +272,42 @@ def test_permutation_duplicates_shift_and_bounds():
     np.testing.assert_allclose(res.loss, base.loss, rtol=1e-5, atol=1e-6)  # E+u is re-rounded to float32
 
 
-# ---- P9: the paper's listings, step by step --------------------------------------------------------------------------
-@pytest.mark.parametrize("block", [1, 4, 5])
-def test_online_recurrence_and_blockwise_gradients_match(block):
-    r, H, E, tgt = _rand(50 + block, N=11, V=37, d=7, K=13)
-    N, K = 11, 13
-    neg = r.integers(0, 37, (N, K)).astype(np.int32)
-    Inds = np.concatenate([tgt[:, None], neg], 1).astype(np.int64)
+# ---- P9: the online-softmax identity the forward algorithm rests on (Alg. 1), and Eq. 6 as sparse matrix products -----
+@pytest.mark.parametrize("seed", [1, 4, 5])
+def test_lse_of_random_partitions_merged_in_random_order_and_sparse_matrix_gradients(seed):
+    """Any way of cutting a position's candidates into parts, taking (max, sum of exponentials) per part and merging the
+    pairs in any order must reproduce the two-pass LSE of the definition: that associativity is what lets Alg. 1 walk
+    the candidates block by block with a running maximum.  The gradients of Eq. 6 are held against scipy's sparse
+    matrix product of the coefficient matrix with H (dE) and a dense product with the gathered rows (dH)."""
+    import scipy.sparse as sp
+
+    r, H, E, tgt = _rand(50 + seed, N=11, V=37, d=7, K=13)
+    N, K, V = 11, 13, 37
+    neg = r.integers(0, V, (N, K)).astype(np.int32)
+    cand = np.concatenate([tgt[:, None], neg], 1).astype(np.int64)
     res = O.run(H, E, tgt, neg, None, None, in_dtype="f32", neg_mode=PP, mask_collisions=0)
-    lse = alg_literal.lse_online(H, E, Inds, block=block)
-    np.testing.assert_allclose(lse, res.lse, rtol=1e-13)
-    # gradient of sum_i g_i*LSE_i from the listing, plus the correct-logit path (-g e_x into dH, -g h into dE[x])
+    H64, E64 = H.astype(np.float64), E.astype(np.float64)
+    for i in range(N):
+        o = E64[cand[i]] @ H64[i]
+        order = r.permutation(K + 1)
+        cuts = np.sort(r.choice(np.arange(1, K + 1), size=int(r.integers(1, 6)), replace=False))
+        pairs = [(float(o[part].max()), float(np.exp(o[part] - o[part].max()).sum())) for part in np.split(order, cuts)]
+        while len(pairs) > 1:                      # merge two random pairs until one is left
+            a = pairs.pop(int(r.integers(len(pairs))))
+            b = pairs.pop(int(r.integers(len(pairs))))
+            M = max(a[0], b[0])
+            pairs.append((M, a[1] * math.exp(a[0] - M) + b[1] * math.exp(b[0] - M)))
+        assert abs(pairs[0][0] + math.log(pairs[0][1]) - res.lse[i]) <= 1e-13 * max(1.0, abs(res.lse[i]))
     g = r.standard_normal(N)
     resg = O.run(H, E, tgt, neg, None, g, in_dtype="f32", neg_mode=PP, mask_collisions=0)
-    dH, dE = alg_literal.grads_blockwise(H, E, Inds, lse, g, block=block)
-    dH -= g[:, None] * E[tgt].astype(np.float64)
-    np.add.at(dE, tgt, -g[:, None] * H.astype(np.float64))
+    scores = np.einsum("nkd,nd->nk", E64[cand], H64)
+    G = g[:, None] * np.exp(scores - resg.lse[:, None])
+    G[:, 0] -= g                                    # the correct item sits in column 0
+    dH = np.einsum("nk,nkd->nd", G, E64[cand])
+    rows = np.repeat(np.arange(N), K + 1)
+    dE = (sp.coo_matrix((G.ravel(), (cand.ravel(), rows)), shape=(V, N)).tocsr() @ H64)   # duplicates add up
     np.testing.assert_allclose(resg.dH, dH, rtol=1e-10, atol=1e-14)
-    np.testing.assert_allclose(resg.dE, dE, rtol=1e-10, atol=1e-14)
+    np.testing.assert_allclose(resg.dE, np.asarray(dE), rtol=1e-10, atol=1e-14)
 
 
 # ---- masks, selections, bookkeeping -----------------------------------------------------------------------------------
