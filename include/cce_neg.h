@@ -142,6 +142,28 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * cce_neg_forward for callers that can hand over no workspace and must not allocate: code under HIP graph capture,
+ * tight serving loops (scoring a batch needs the forward pass only), harnesses that forbid allocation.  Same inputs,
+ * outputs and results as cce_neg_forward; the scratch memory the kernels need (compaction of padded positions,
+ * collision counts, partial max / sum of split launches) lives in a fixed array inside the library's code object,
+ * CCE_NEG_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends.  Nothing is allocated or freed by the call:
+ * the array's device address is looked up once per device (hipGetSymbolAddress, on the first call with that device
+ * current; make that first call outside a graph capture) and a small fill kernel clears the array's header, which
+ * keeps whatever the last call left there.
+ *   - A descriptor whose forward pass needs more scratch than the array holds is refused with CCE_ERR_WORKSPACE
+ *     before anything is launched.  Matrix-core path: 20 bytes per position, plus 8 per position and split where the
+ *     candidate range is split (at most 8 ways), so 32 MiB carry between 390,000 and 1,600,000 positions; other
+ *     paths need 256 bytes.  validate_indices = 1 is refused with CCE_ERR_UNSUPPORTED (there is no status
+ *     word the caller could read).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race.
+ *     Calls on one stream are ordered and safe.
+ *   - A backward call cannot reuse what this call left (reuse_forward_prep needs a caller-owned workspace).
+ */
+#define CCE_NEG_NOALLOC_SCRATCH_BYTES (32u << 20)
+cce_status cce_neg_forward_noalloc(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt,
+                                   const int32_t *neg, const uint8_t *mask, float *loss, float *lse, void *hip_stream);
+
+/*
  * Negative sampling inside the kernels.  The paper draws the negatives of a step on the host (global uniform sampling,
  * or popularity-based sampling through a multinomial over the catalogue: Sec. 5, "Comparison Sampling Strategies")
  * and names the stored index matrix as the memory cost of CCE- over CCE (Sec. 5, "What is better").  The *_sampled

@@ -25,7 +25,7 @@ CCE_SAMPLER_UNIFORM, CCE_SAMPLER_ALIAS = 1, 2
 EXPORTS = (
     "cce_neg_workspace_bytes", "cce_neg_workspace_init", "cce_neg_forward", "cce_neg_backward",
     "cce_neg_index_status", "cce_status_string", "cce_neg_profile_enable", "cce_neg_profile_read",
-    "cce_neg_sample", "cce_neg_forward_sampled", "cce_neg_backward_sampled",
+    "cce_neg_sample", "cce_neg_forward_sampled", "cce_neg_backward_sampled", "cce_neg_forward_noalloc",
 )
 
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.cce_neg_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
         L.cce_neg_forward.restype = ctypes.c_int
         L.cce_neg_forward.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.cce_neg_forward_noalloc.restype = ctypes.c_int
+        L.cce_neg_forward_noalloc.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp]
         L.cce_neg_backward.restype = ctypes.c_int
         L.cce_neg_backward.argtypes = [ctypes.POINTER(CceDesc), vp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp,
                                        ctypes.c_size_t, vp]
@@ -184,6 +186,16 @@ def cce_neg_forward(desc: CceDesc, H, E, tgt, neg, mask, loss, lse, workspace, *
                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     if check and st != CCE_OK:
         raise CceError(st, "cce_neg_forward")
+    return st
+
+
+def cce_neg_forward_noalloc(desc: CceDesc, H, E, tgt, neg, mask, loss, lse, *, check: bool = True) -> int:
+    """cce_neg_forward on the library's own fixed scratch array: no workspace, no allocation (see include/cce_neg.h)."""
+    check_step_args(desc, H, E, tgt, neg, mask, loss=loss, lse=lse)
+    st = lib().cce_neg_forward_noalloc(ctypes.byref(desc), _ptr(H), _ptr(E), _ptr(tgt), _ptr(neg), _ptr(mask), _ptr(loss),
+                                       _ptr(lse), _stream())
+    if check and st != CCE_OK:
+        raise CceError(st, "cce_neg_forward_noalloc")
     return st
 
 

@@ -3,6 +3,7 @@
 #include <math.h>
 
 #include <string.h>
+#include <mutex>
 #include <vector>
 
 #include "cce_device.hpp"
@@ -12,6 +13,7 @@ namespace cce {
 namespace {
 
 constexpr size_t kHeaderBytes = 256;  // status word, compaction counters; keeps what follows 256-byte aligned
+constexpr int kMaxScratchDevices = 64;
 
 size_t align256(size_t n) { return (n + 255) & ~size_t(255); }
 
@@ -219,6 +221,14 @@ PrepArgs make_prep_args(const cce_desc *d, const Layout &L, const int32_t *tgt, 
     return p;
 }
 
+// What a forward call alone touches of the workspace: everything in front of the partial dH rows on the matrix-core
+// path, the header otherwise (the inverted index and the coefficients of the per-position layout are the backward
+// call's).
+size_t forward_scratch_bytes(const cce_desc *d)
+{
+    return use_tile(d) ? make_layout(d).part_dH : kHeaderBytes;
+}
+
 // Shared mode: the sampled calls write their K ids behind everything else in the workspace.
 size_t shared_ids_offset(const cce_desc *d)
 {
@@ -319,8 +329,35 @@ cce_status cce_neg_workspace_init(void *workspace, size_t workspace_bytes, void 
 
 }  // extern "C"
 
+// ---- scratch of the entry point that takes no workspace: one array per GPU, held until the process ends
 namespace cce {
 namespace {
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+}
+}  // namespace cce
+// In host code this name only stands for the symbol; its device address comes from hipGetSymbolAddress (below).
+static __device__ __align__(256) unsigned char scratch[cce::kStaticScratchBytes];
+
+namespace cce {
+namespace {
+
+// Device address of `scratch` on the current device, looked up once per device (every GPU holds its own copy of the
+// array at its own address) and kept.  Not an allocation: the array is part of the library's code object.
+cce_status static_scratch(void **out)
+{
+    static std::mutex lock;
+    static void *ptr[kMaxScratchDevices];  // nullptr = not looked up yet
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return CCE_ERR_HIP;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CCE_ERR_HIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return CCE_OK;
+}
 
 // Shared mode of the sampled calls: draw the K ids into the workspace and hand them on as a stored list.
 // Per-position mode: the kernels draw; `neg` stays NULL.
@@ -481,6 +518,24 @@ cce_status cce_neg_backward(const cce_desc *desc, const void *H, const void *E, 
     if (!lse || !dH || !dE) return CCE_ERR_NULL;
     return cce::backward_impl(desc, cce::Sampler{}, H, E, tgt, neg, mask, lse, grad_loss, dH, dE, workspace,
                               static_cast<hipStream_t>(hip_stream));
+}
+
+cce_status cce_neg_forward_noalloc(const cce_desc *desc, const void *H, const void *E, const int32_t *tgt,
+                                   const int32_t *neg, const uint8_t *mask, float *loss, float *lse, void *hip_stream)
+{
+    cce_status st = cce::check_desc(desc);
+    if (st != CCE_OK) return st;
+    if (!H || !E || !tgt || !loss || !lse) return CCE_ERR_NULL;
+    if (desc->neg_mode != CCE_NEG_FULL && desc->K > 0 && !neg) return CCE_ERR_NULL;
+    if (desc->validate_indices) return CCE_ERR_UNSUPPORTED;  // no status word the caller could read afterwards
+    if (cce::forward_scratch_bytes(desc) > cce::kStaticScratchBytes) return CCE_ERR_WORKSPACE;
+    void *ws = nullptr;
+    st = cce::static_scratch(&ws);
+    if (st != CCE_OK) return st;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // the array keeps what the last call left: the header (status word, counters) starts from zero every time
+    if (cce::launch_fill_zero(static_cast<int32_t *>(ws), cce::kHeaderBytes / 4, stream) != hipSuccess) return CCE_ERR_HIP;
+    return cce::forward_impl(desc, cce::Sampler{}, H, E, tgt, neg, mask, loss, lse, ws, stream);
 }
 
 cce_status cce_neg_sample(const cce_desc *desc, const cce_sampler *sampler, int32_t *neg_out, void *hip_stream)

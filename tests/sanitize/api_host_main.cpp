@@ -25,6 +25,8 @@ hipError_t __hipPushCallConfiguration(dim3, dim3, size_t, hipStream_t) { return 
 hipError_t __hipPopCallConfiguration(dim3 *, dim3 *, size_t *, hipStream_t *) { return hipSuccess; }
 hipError_t hipLaunchKernel(const void *, dim3, dim3, void **, size_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t hipGetLastError(void) { return hipSuccess; }
+void __hipRegisterVar(void **, void *, char *, char *, int, size_t, int, int) {}
+hipError_t hipGetSymbolAddress(void **p, const void *) { alignas(256) static char stand_in[256]; *p = stand_in; return hipSuccess; }
 hipError_t hipGetDevice(int *dev) { *dev = 0; return hipSuccess; }
 hipError_t hipDeviceGetAttribute(int *v, hipDeviceAttribute_t, int) { *v = 256; return hipSuccess; }
 hipError_t hipOccupancyMaxActiveBlocksPerMultiprocessor(int *n, const void *, int, size_t) { *n = 2; return hipSuccess; }
@@ -93,6 +95,15 @@ int main()
         CHECK(cce_neg_backward(&x, fake, fake, ids, ids, nullptr, fl, nullptr, fake, fl, fake, sizeof arena, nullptr) == b.want);
     }
     CHECK(cce_neg_workspace_bytes(nullptr) == 0);
+    {   // the entry point on the library's own scratch: size limit, refusals, and a call that goes through
+        cce_desc x = desc_of(2000000, 1000, 64, 256, CCE_BF16, CCE_NEG_SHARED);
+        CHECK(cce_neg_forward_noalloc(&x, fake, fake, ids, ids, nullptr, fl, fl, nullptr) == CCE_ERR_WORKSPACE);
+        x = desc_of(1000, 1000, 64, 256, CCE_BF16, CCE_NEG_SHARED);
+        CHECK(cce_neg_forward_noalloc(&x, fake, fake, ids, ids, nullptr, fl, fl, nullptr) == CCE_OK);
+        CHECK(cce_neg_forward_noalloc(&x, fake, fake, ids, nullptr, nullptr, fl, fl, nullptr) == CCE_ERR_NULL);
+        x.validate_indices = 1;
+        CHECK(cce_neg_forward_noalloc(&x, fake, fake, ids, ids, nullptr, fl, fl, nullptr) == CCE_ERR_UNSUPPORTED);
+    }
     CHECK(cce_neg_forward(nullptr, fake, fake, ids, ids, nullptr, fl, fl, fake, 4096, nullptr) == CCE_ERR_NULL);
     cce_desc f = desc_of(256, 1000, 64, 0, CCE_BF16, CCE_NEG_FULL);
     f.filter_eps = 1e-4f;
