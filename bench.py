@@ -69,12 +69,16 @@ def kernel_work(w, family):
     gemm = 2.0 * n_cols * w.d * nv
     if family == "tile_fwd":
         return "mfma", gemm
-    if family == "tile_dh":
+    if family in ("tile_dh", "tile_fdh"):   # scores + dH; the fused forward + dH pass (fuse_dH) is the same two
         return "mfma", 2 * gemm
     if family == "tile_de":
         return "mfma", gemm
     if family == "tile_bwd":   # dH and dE pass in one launch
         return "mfma", 3 * gemm
+    if family == "dh_scale":   # U read, dH written (fp32 both), grad_loss
+        return "hbm", float(nv) * (8 * w.d + 4) + w.N
+    if family == "fdh_merge":  # partial rows read once, U written
+        return "hbm", float(nv) * 8 * w.d
     if family == "bwd_pre":    # per valid position: H row, correct item's row, five scalars in, three out
         return "hbm", float(nv) * (2 * w.d * esz + 32)
     n_cand = w.V if w.neg_mode == 2 else w.K + 1
@@ -126,13 +130,14 @@ def measure(w, args, *, headline: bool) -> dict:
     algo = {"auto": P.CCE_ALGO_AUTO, "gather": P.CCE_ALGO_GATHER, "tile": P.CCE_ALGO_TILE}[args.algo]
     in_dt = P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16
     filter_eps = args.filter_eps if headline else 0.0
+    fuse = 0 if (args.no_fuse_dh or filter_eps > 0) else 1
     desc = P.make_desc(w.N, w.V, w.d, w.K, in_dt, w.neg_mode, mask_target_collisions=w.mask_collisions,
-                       validate_indices=0, algo=algo)
+                       validate_indices=0, algo=algo, fuse_dH=fuse)
     # a training step runs the backward pass right after the forward pass of the same batch on the same workspace:
     # the backward call may then reuse what the forward call left there
     desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, in_dt, w.neg_mode, mask_target_collisions=w.mask_collisions,
                            validate_indices=0, algo=algo, reuse_forward_prep=0 if args.no_reuse_prep else 1,
-                           filter_eps=filter_eps)
+                           filter_eps=filter_eps, fuse_dH=fuse)
     ws = P.new_workspace(desc)
     loss = torch.empty(w.N, device="cuda")
     lse = torch.empty(w.N, device="cuda")
@@ -254,7 +259,7 @@ def measure(w, args, *, headline: bool) -> dict:
     config = {
         "workload": w.name, "N": w.N, "n_valid": w.n_valid, "d": w.d, "V": w.V, "K": w.K,
         "neg_mode": ["shared", "per_position", "full"][w.neg_mode], "algo": args.algo,
-        "reuse_forward_prep": not args.no_reuse_prep, "filter_eps": filter_eps, "sampler": sampler,
+        "reuse_forward_prep": not args.no_reuse_prep, "fuse_dH": bool(fuse), "filter_eps": filter_eps, "sampler": sampler,
         "valid_positions_per_s": w.n_valid / (ms_step * 1e-3),
         "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cold_ms_per_step": cold_ms, "dE_zero_fill_ms": memset_ms, "kernels": kernels,
         "exp_ceiling_ms": 2.0 * w.n_valid * ((w.V if w.neg_mode == 2 else w.K) + 1) / EXP_PER_S * 1e3,
@@ -287,6 +292,9 @@ def main() -> int:
     ap.add_argument("--filter-eps", type=float, default=0.0, help="gradient filtering threshold (full-catalogue workload c4 only)")
     ap.add_argument("--peaked", action="store_true", help="hidden states that point at their target row: a concentrated softmax, as late in training (c4)")
     ap.add_argument("--no-reuse-prep", action="store_true", help="backward recomputes what the forward call left in the workspace")
+    ap.add_argument("--no-fuse-dh", action="store_true",
+                    help="forward computes lse only and the backward call runs a dH pass of its own (five score-sized products "
+                         "per step instead of four)")
     ap.add_argument("--sampler", default="none", choices=["none", "uniform", "alias"],
                     help="draw the negatives inside the kernels (shared / per-position workloads): no index array is read")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target oracle time for the cpu_baseline sample")

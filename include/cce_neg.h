@@ -89,10 +89,23 @@ typedef struct {
                                        zero in Eq. 6 (it adds nothing to dH or dE; the term of the correct item stays).
                                        loss and lse are exact.  Needs CCE_NEG_FULL, bf16 inputs and d in {64,128,256},
                                        else CCE_ERR_UNSUPPORTED; negative or NaN: CCE_ERR_SHAPE. */
+    int32_t fuse_dH;                /* 1: the forward call also forms the hidden-state gradient short of the upstream
+                                       gradient, U_i = sum_j softmax_ij E_cij - E_tgt_i (Eq. 6 left with grad LSE = 1 and the
+                                       correct item's term), in the same pass over the candidates that yields lse (an
+                                       online softmax: no log-sum-exp is known yet, the rows are divided by the sum at the
+                                       end), and keeps it in the workspace (4 N d bytes more); a backward call with this
+                                       flag AND reuse_forward_prep = 1 then writes dH_i = grad_loss_i U_i and computes the
+                                       scores once more for dE only: four products of the size of the score matrix per
+                                       step instead of five, two exponentials per score instead of three.  Set it the
+                                       same way in the size query, the forward and the backward descriptor.  Matrix-core
+                                       path only (bf16, shared or full mode, d in {64,128,256}); ignored elsewhere, and
+                                       by a backward call without reuse_forward_prep or with filter_eps > 0 (those run
+                                       the dH pass as without the flag).  A forward-only caller leaves it 0. */
 } cce_desc;
 
 /* Bytes of device workspace both calls need for this descriptor.  Returns 0 for an invalid descriptor.
- *   shared / full mode, bf16:  20 bytes per position (compaction, collision counts, coefficients), plus partial
+ *   shared / full mode, bf16:  20 bytes per position (compaction, collision counts, coefficients), 4 d more with fuse_dH,
+ *                              plus partial
  *                              results of split launches: 8 bytes per position and forward split, and, for batches
  *                              of at most 40,960 positions, 4 d bytes per position and dH split; hidden size 256 and
  *                              more than 65,536 positions: 64 MiB of partial dH rows for the split of the last round

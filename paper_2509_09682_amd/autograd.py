@@ -20,7 +20,7 @@ _serial = 0
 def _workspace(desc: B.CceDesc, device):
     """One workspace per descriptor shape and device; forward and backward of a step share it."""
     key = (desc.N, desc.V, desc.d, desc.K, desc.in_dtype, desc.dH_dtype, desc.neg_mode, desc.mask_target_collisions,
-           desc.validate_indices, desc.algo, str(device))
+           desc.validate_indices, desc.algo, desc.fuse_dH, str(device))
     ws = _workspaces.get(key)
     if ws is None:
         ws = _workspaces[key] = B.new_workspace(desc, device=device)
@@ -39,7 +39,10 @@ class _CceNegLoss(torch.autograd.Function):
         else:
             K = 0 if neg is None or neg_mode == B.CCE_NEG_FULL else int(neg.shape[-1])
         dt = B.CCE_F32 if H.dtype == torch.float32 else B.CCE_BF16
-        kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0)
+        # fuse_dH: the forward call also forms the hidden-state gradient short of grad_loss (one pass over the candidates
+        # less per step); only worth it when a backward call will follow, and not with gradient filtering
+        fuse = 1 if ((H.requires_grad or E.requires_grad) and not filter_eps > 0) else 0
+        kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0, fuse_dH=fuse)
         desc = B.make_desc(N, V, d, K, dt, neg_mode, **kw)
         B.check_step_args(desc, H, E, tgt, neg, mask, sampled=sampler is not None)   # before anything touches the device
         global _serial

@@ -34,7 +34,7 @@ class CceDesc(ctypes.Structure):
         ("N", ctypes.c_int64), ("V", ctypes.c_int64), ("d", ctypes.c_int32), ("K", ctypes.c_int32),
         ("in_dtype", ctypes.c_int32), ("dH_dtype", ctypes.c_int32), ("neg_mode", ctypes.c_int32),
         ("mask_target_collisions", ctypes.c_int32), ("validate_indices", ctypes.c_int32), ("algo", ctypes.c_int32),
-        ("reuse_forward_prep", ctypes.c_int32), ("filter_eps", ctypes.c_float),
+        ("reuse_forward_prep", ctypes.c_int32), ("filter_eps", ctypes.c_float), ("fuse_dH", ctypes.c_int32),
     ]
 
 
@@ -100,10 +100,10 @@ def status_string(status: int) -> str:
 
 def make_desc(N: int, V: int, d: int, K: int, in_dtype: int, neg_mode: int, *, dH_dtype: Optional[int] = None,
               mask_target_collisions: int = 1, validate_indices: int = 0, algo: int = CCE_ALGO_AUTO,
-              reuse_forward_prep: int = 0, filter_eps: float = 0.0) -> CceDesc:
+              reuse_forward_prep: int = 0, filter_eps: float = 0.0, fuse_dH: int = 0) -> CceDesc:
     return CceDesc(int(N), int(V), int(d), int(K), int(in_dtype), int(CCE_F32 if dH_dtype is None else dH_dtype),
                    int(neg_mode), int(mask_target_collisions), int(validate_indices), int(algo), int(reuse_forward_prep),
-                   float(filter_eps))
+                   float(filter_eps), int(fuse_dH))
 
 
 def _ptr(t: Optional[torch.Tensor]):

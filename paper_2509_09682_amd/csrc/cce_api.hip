@@ -8,6 +8,7 @@
 
 #include "cce_device.hpp"
 #include "cce_kernels.hpp"
+#include "cce_tile_shared.hpp"
 
 namespace cce {
 namespace {
@@ -25,11 +26,13 @@ bool tile_eligible(const cce_desc *d)
     return n_cols >= 1;
 }
 bool use_tile(const cce_desc *d) { return d->algo != CCE_ALGO_GATHER && tile_eligible(d); }
+// The forward call forms the hidden-state gradient as well (fuse_dH), where the matrix-core path runs.
+bool fused_dH(const cce_desc *d) { return d->fuse_dH != 0 && use_tile(d); }
 
 // Workspace layout of the matrix-core path.  Split factors depend on the descriptor only, so that the size query and
 // the launches agree.
 struct Layout {
-    size_t idx, cnt, coef, de_const, part_m, part_s, part_dH, total;
+    size_t idx, cnt, coef, de_const, part_m, part_s, part_dH, U, total;
     int splits_x;   // dH pass: candidate range split over at most this many blocks per position block
     int splits_fwd; // forward pass: the same, with its own (cheaper) bound
     int splits_de;  // dE pass: position range split
@@ -71,13 +74,21 @@ Layout make_layout(const cce_desc *d)
     L.cnt = off;      off += align256((size_t)N * 4);
     L.coef = off;     off += align256((size_t)N * 4);
     L.de_const = off; off += align256((size_t)N * 8);
-    L.part_m = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
-    L.part_s = off;   off += (sf > 1) ? align256((size_t)sf * N * 4) : 0;
+    {
+        // partial (max, sum) per position and split; the fused forward pass also files them for the rows of its
+        // last-round split (at most kTailRows of them)
+        size_t words = (sf > 1) ? (size_t)sf * N : 0;
+        if (fused_dH(d) && tile_tail_partial_bytes(N, d->d) > 0 && words < (size_t)kTailRows) words = (size_t)kTailRows;
+        L.part_m = off;   off += align256(words * 4);
+        L.part_s = off;   off += align256(words * 4);
+    }
     {
         const size_t split_bytes = (sx > 1) ? (size_t)sx * N * d->d * 4 : 0, tail_bytes = tile_tail_partial_bytes(N, d->d);
         L.part_dH = off;
         off += align256(split_bytes > tail_bytes ? split_bytes : tail_bytes);
     }
+    L.U = off;
+    if (fused_dH(d)) off += align256((size_t)N * d->d * 4);
     L.total = off;
     return L;
 }
@@ -188,6 +199,7 @@ TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const
     a.part_m = reinterpret_cast<float *>(ws + L.part_m);
     a.part_s = reinterpret_cast<float *>(ws + L.part_s);
     a.part_dH = reinterpret_cast<float *>(ws + L.part_dH);
+    a.U = fused_dH(d) ? reinterpret_cast<float *>(ws + L.U) : nullptr;
     a.N = d->N;
     a.V = d->V;
     a.n_cols = shared ? d->K : d->V;
@@ -273,7 +285,8 @@ bool g_prof_enabled = false;
 std::vector<ProfRecord> g_prof_records;
 std::vector<hipEvent_t> g_prof_pool;
 const char *const kProfNames[PROF_FAMILIES] = {"gather_fwd", "gather_bwd", "prep",  "tile_fwd", "fwd_merge",  "tile_dh",
-                                               "dh_merge",   "tile_de",    "index", "item_de",  "pos_scatter", "bwd_pre", "tile_bwd"};
+                                               "dh_merge",   "tile_de",    "index", "item_de",  "pos_scatter", "bwd_pre", "tile_bwd",
+                                               "tile_fdh",   "fdh_merge",  "dh_scale"};
 hipEvent_t prof_event()
 {
     if (!g_prof_pool.empty()) {
@@ -393,6 +406,10 @@ cce_status forward_impl(const cce_desc *desc, const Sampler &smp, const void *H,
         cce::TileArgs a = cce::make_tile_args(desc, L, H, E, tgt, neg, mask, workspace);
         a.loss = loss;
         a.lse = lse;
+        if (cce::fused_dH(desc)) {  // lse and the hidden-state gradient short of grad_loss in one pass (splits as the dH pass)
+            a.splits = L.splits_x;
+            return cce::launch_tile(cce::TILE_PASS_FDH, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+        }
         a.splits = L.splits_fwd;
         return cce::launch_tile(cce::TILE_PASS_FWD, a, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
     }
@@ -429,6 +446,20 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
         a.g_separate = (desc->reuse_forward_prep && grad_loss && cce::tile_backward_fusable(desc->d)) ? 1 : 0;
         cce::TileArgs a_de = a;
         a_de.splits = L.splits_de;
+        if (cce::fused_dH(desc) && desc->reuse_forward_prep && !(desc->filter_eps > 0.f)) {
+            // The forward call left U, the correct items' coefficients and the exponent offsets of the dE pass: dH is
+            // grad_loss * U, and the scores are recomputed for dE alone.  Where the dE pass streams grad_loss by row
+            // number (hidden sizes up to 128, grad_loss given) the scaling rides in its launch; otherwise it goes first
+            // and files grad_loss under the compacted index on the way.
+            a_de.g_separate = 1;  // the scatter multiplies the forward call's coefficient by grad_loss itself
+            if (cce::tile_backward_fusable(desc->d) && grad_loss) {
+                a_de.scale_blocks = 1;
+                return cce::launch_tile(cce::TILE_PASS_DE, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+            }
+            if (cce::launch_dh_scale(a, true, stream) != hipSuccess) return CCE_ERR_HIP;
+            a_de.g_stream_off = 1;  // the dE pass reads grad_loss where the scaling pass has just filed it
+            return cce::launch_tile(cce::TILE_PASS_DE, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+        }
         if (cce::tile_backward_fusable(desc->d))  // both passes in one launch, behind a small per-position pass
             return cce::launch_tile_backward(a, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
         if (cce::launch_tile(cce::TILE_PASS_DH, a, stream) != hipSuccess) return CCE_ERR_HIP;
@@ -528,6 +559,7 @@ cce_status cce_neg_forward_noalloc(const cce_desc *desc, const void *H, const vo
     if (!H || !E || !tgt || !loss || !lse) return CCE_ERR_NULL;
     if (desc->neg_mode != CCE_NEG_FULL && desc->K > 0 && !neg) return CCE_ERR_NULL;
     if (desc->validate_indices) return CCE_ERR_UNSUPPORTED;  // no status word the caller could read afterwards
+    if (desc->fuse_dH) return CCE_ERR_UNSUPPORTED;           // the rows it would keep belong in a caller-owned workspace
     if (cce::forward_scratch_bytes(desc) > cce::kStaticScratchBytes) return CCE_ERR_WORKSPACE;
     void *ws = nullptr;
     st = cce::static_scratch(&ws);

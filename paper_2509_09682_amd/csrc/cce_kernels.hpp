@@ -42,11 +42,16 @@ struct TileArgs {
     float *coef;                 // [N] coefficient of the correct item, written by the dH pass, read by the scatter
     uint32_t *de_const;          // [2, N] per compacted position (float bits): exponent offset -lse log2e and upstream
                                  // gradient g of the dE coefficient; written ahead of the dE pass, streamed by it
+    float *U;                    // [N, d] fused forward pass (out), dH scaling (in): the hidden-state gradient short of the
+                                 // upstream gradient, U_i = sum_j p_ij E_cij - E_tgt_i, filed under the position's row
     float *part_m, *part_s;      // [splits, N] partial max / sum of split forward runs
     float *part_dH;              // [splits, N, d] partial dH of split runs
     int64_t N, V, n_cols;        // n_cols = K, or V in full-catalogue mode
     int64_t pos_blocks;          // dE launch: blocks [0, pos_blocks) scatter the correct items, the rest run the dE pass
     int64_t pad_blocks;          // dH launch: blocks [0, pad_blocks) zero the dH rows of padded positions (set by the launcher)
+    int64_t scale_block0;        // dE launch: blocks from this one on write dH = grad_loss * U (set by the launcher; none
+                                 // when scale_blocks is 0)
+    int64_t scale_blocks;
     int32_t d, splits, pos_weight_mode, dH_bf16, validate;  // splits: upper bound on entry to launch_tile, chosen factor inside
     int32_t write_consts;        // dH pass: 1 = it files coef and de_const itself (dE launched after it), 0 = a pass before it did
     float filter_log2;           // backward, gradient filtering: log2 of the threshold; -inf = off
@@ -54,11 +59,17 @@ struct TileArgs {
     int32_t tail_slots;          // dH pass, > 0: blocks the chip holds at once; the position blocks of the last, partly filled
                                  // round split the candidate range among the idle block slots (planned on the device from
                                  // the count of valid positions), partial rows in part_dH, summed by the tail merge
+    int32_t g_stream_off;        // dE pass with g_separate: 1 = grad_loss is NOT streamed by row number but read from the second
+                                 // half of de_const, where a pass before this one filed it under the compacted index
     int32_t g_separate;          // backward: coef and de_const[0] are what the FORWARD pass left (no upstream gradient in
                                  // them): the scatter multiplies by g itself and the dE pass streams g by row number
 };
 
-enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2 };  // the dE launch also scatters the correct items
+// The dE launch also scatters the correct items.  FDH: forward pass that also forms U (TileArgs::U) with an online softmax.
+enum { TILE_PASS_FWD = 0, TILE_PASS_DH = 1, TILE_PASS_DE = 2, TILE_PASS_FDH = 3 };
+// dH = grad_loss * U for valid positions, zero rows for padded ones, as a launch of its own; with file_g the upstream
+// gradient is also filed under the compacted index (second half of de_const) for a dE pass that does not stream it by row.
+hipError_t launch_dh_scale(const TileArgs &a, bool file_g, hipStream_t stream);
 // dH and dE passes in one launch (hidden sizes up to 128): a_dh.splits / a_de.splits carry the two split bounds.
 bool tile_backward_fusable(int d);
 hipError_t launch_tile_backward(const TileArgs &a_dh, const TileArgs &a_de, hipStream_t stream);
@@ -104,7 +115,8 @@ hipError_t launch_tile(int pass, const TileArgs &a, hipStream_t stream);
 
 // Event bracket around a kernel launch while profiling is enabled (see cce_neg_profile_enable); otherwise a no-op.
 enum { PROF_GATHER_FWD = 0, PROF_GATHER_BWD, PROF_PREP, PROF_TILE_FWD, PROF_FWD_MERGE, PROF_TILE_DH, PROF_DH_MERGE,
-       PROF_TILE_DE, PROF_INDEX, PROF_ITEM_DE, PROF_POS_SCATTER, PROF_BWD_PRE, PROF_TILE_BWD, PROF_FAMILIES };
+       PROF_TILE_DE, PROF_INDEX, PROF_ITEM_DE, PROF_POS_SCATTER, PROF_BWD_PRE, PROF_TILE_BWD, PROF_TILE_FDH, PROF_FDH_MERGE,
+       PROF_DH_SCALE, PROF_FAMILIES };
 struct ProfScope {
     ProfScope(int family, hipStream_t stream);
     ~ProfScope();

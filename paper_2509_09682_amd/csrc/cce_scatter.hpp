@@ -70,7 +70,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
     // lane l holds pair l of the wavefront's 64 sorted pairs and its coefficient; the walk broadcasts them lane by lane
     const uint64_t my_key = keys[wave * 64 + lane];
     const uint32_t my_id = (uint32_t)(my_key >> 32), my_row = (uint32_t)my_key;
-    const float my_cf = (my_id != 0xffffffffu) ? a.coef[my_row] * (a.g_separate ? a.g[my_row] : 1.f) : 0.f;
+    const float my_cf = (my_id != 0xffffffffu) ? a.coef[my_row] * ((a.g_separate && a.g) ? a.g[my_row] : 1.f) : 0.f;
     for (int b = 0; b < 64; b += kPosBatch) {
         uint32_t id[kPosBatch];
         float hv[kPosBatch][CPL];

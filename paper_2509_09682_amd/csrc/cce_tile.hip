@@ -156,6 +156,9 @@ hipError_t launch_tile_backward_d128(const TileArgs &a_dh, const TileArgs &a_de,
 hipError_t launch_pos_scatter_d64(const TileArgs &a, hipStream_t stream);
 hipError_t launch_pos_scatter_d128(const TileArgs &a, hipStream_t stream);
 hipError_t launch_pos_scatter_d256(const TileArgs &a, hipStream_t stream);
+hipError_t launch_dh_scale_d64(const TileArgs &a, bool file_g, hipStream_t stream);
+hipError_t launch_dh_scale_d128(const TileArgs &a, bool file_g, hipStream_t stream);
+hipError_t launch_dh_scale_d256(const TileArgs &a, bool file_g, hipStream_t stream);
 
 bool tile_supports_d(int d) { return d == 64 || d == 128 || d == 256; }
 size_t tile_tail_partial_bytes(int64_t N, int d) { return (d > 128 && N > kTailRows) ? (size_t)kTailRows * d * 4 : 0; }
@@ -166,6 +169,16 @@ hipError_t launch_pos_scatter(const TileArgs &a, hipStream_t stream)
     case 64: return launch_pos_scatter_d64(a, stream);
     case 128: return launch_pos_scatter_d128(a, stream);
     case 256: return launch_pos_scatter_d256(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_dh_scale(const TileArgs &a, bool file_g, hipStream_t stream)
+{
+    switch (a.d) {
+    case 64: return launch_dh_scale_d64(a, file_g, stream);
+    case 128: return launch_dh_scale_d128(a, file_g, stream);
+    case 256: return launch_dh_scale_d256(a, file_g, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -42,7 +42,8 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 
-enum { MODE_FWD = 0, MODE_DH = 1, MODE_DE = 2 };
+// MODE_FDH: the forward pass and the hidden-state gradient in one pass over the candidates (see the FDH notes in tile_body).
+enum { MODE_FWD = 0, MODE_DH = 1, MODE_DE = 2, MODE_FDH = 3 };
 
 // Compile-time tags: a full streamed tile, or the short last tile whose missing rows are masked.
 struct Full { static constexpr bool value = false; };
@@ -51,6 +52,9 @@ struct Ragged { static constexpr bool value = true; };
 // the tile began (Lazy: no maximum, no rescaling; the caller repeats the tile exactly if a sum overflowed).
 struct Exact { static constexpr bool lazy = false; };
 struct Lazy { static constexpr bool lazy = true; };
+// The two forms of an attempt at a block's streamed range in the fused forward + dH pass (see the FDH notes in tile_body).
+struct FastTag { static constexpr bool exact = false; };
+struct ExactTag { static constexpr bool exact = true; };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)
 {
@@ -162,6 +166,42 @@ __device__ __forceinline__ float max3_after(float after, float x, float y, float
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(y), "v"(z), "v"(after));
     return r;
+}
+
+constexpr int kScaleChunks = 4;  // 32-byte pieces of dH per thread of a scaling block
+
+// dH = grad_loss * U for the valid positions, zero rows for the padded ones: one lane per 8 columns, positions in their
+// original order.  FILE_G: the first blocks also file the upstream gradient under the compacted index (second half of
+// de_const), where a dE pass that does not stream it by row number finds it.
+template <int D>
+__device__ __forceinline__ void dh_scale_chunk(const TileArgs &a, int64_t chunk)
+{
+    constexpr int LPR = D / 8;
+    const int64_t i = chunk / LPR;
+    const int c = (int)(chunk % LPR);
+    if (i >= a.N) return;
+    bool valid = (a.pos_mask == nullptr) || (a.pos_mask[i] != 0);
+    if (valid && a.validate) {  // a position with a target out of range counts as padding
+        const int32_t ti = a.tgt[i];
+        valid = ti >= 0 && (int64_t)ti < a.V;
+    }
+    float v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = 0.f;
+    if (valid) {
+        const float g = a.g ? a.g[i] : 1.f;
+        load8(a.U + i * D + c * 8, v);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= g;
+    }
+    if (a.dH_bf16) {
+        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(a.dH) + i * D + c * 8) =
+            make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+    } else {
+        float4 *out = reinterpret_cast<float4 *>(static_cast<float *>(a.dH) + i * D + c * 8);
+        out[0] = make_float4(v[0], v[1], v[2], v[3]);
+        out[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
 }
 
 // D: hidden size.  BY: streamed rows per LDS tile.  NW: wavefronts per block.  XG: groups of 32 stationary rows per
@@ -277,6 +317,12 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         pos_scatter_block<D>(a, block_id, reinterpret_cast<uint64_t *>(buf0));
         return;
     }
+    if (MODE == MODE_DE && a.scale_blocks > 0 && block_id >= a.scale_block0) {  // trailing blocks: dH = grad_loss * U
+#pragma unroll
+        for (int j = 0; j < kScaleChunks; ++j)
+            dh_scale_chunk<D>(a, ((block_id - a.scale_block0) * kScaleChunks + j) * (NW * 64) + tid);
+        return;
+    }
     if (MODE == MODE_DH && block_id < a.pad_blocks) {  // leading blocks: dH rows of padded positions are zero
         const int64_t i = block_id * (NW * 64) + tid;
         if (i < a.N) {
@@ -306,7 +352,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     int split = (int)(bid % a.splits), splits = a.splits;
     int64_t xb = bid / a.splits;
     int64_t part_rows = a.N, part_x0 = 0;  // partial dH rows of split runs: rows per split, first position filed there
-    if (MODE == MODE_DH && a.tail_slots > 0) {  // last-round split, planned from the device-side count (a.splits == 1)
+    if ((MODE == MODE_DH || MODE == MODE_FDH) && a.tail_slots > 0) {  // last-round split, planned from the device-side count (a.splits == 1)
         const TailPlan tp = tail_plan((n_x + XPB - 1) / XPB, a.tail_slots);
         if (bid >= tp.whole) {
             xb = tp.whole + (bid - tp.whole) / tp.splits;
@@ -386,7 +432,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     auto const_row_slot = [&]() -> int { return ((wave % CI) * 64 + lane) % BY; };
     auto rows_from_global = [&](int64_t t, int32_t (&rows)[NR]) {
         rows[LPW] = 0;
-        if (GSEP && a.g_separate) {
+        if (GSEP && a.g_separate && !a.g_stream_off) {
             int64_t y = t * BY + const_row_slot();
             if (y >= n_y) y = n_y - 1;
             rows[LPW] = ind ? ind[y] : (int32_t)y;
@@ -402,7 +448,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     auto rows_from_lds = [&](int64_t t, const uint16_t *holder, int32_t (&rows)[NR]) {
         const int32_t *ids = reinterpret_cast<const int32_t *>(holder + OFF_I);
         rows[LPW] = 0;
-        if (GSEP && a.g_separate) {
+        if (GSEP && a.g_separate && !a.g_stream_off) {
             const int64_t y = t * BY + const_row_slot();
             rows[LPW] = ind ? ids[const_row_slot()] : (int32_t)(y < n_y ? y : n_y - 1);
         }
@@ -461,7 +507,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             if (y > last_y) y = last_y;
             const uint32_t *src = a.de_const + (int64_t)(e / BY) * a.N + y;
             // upstream gradient straight from the caller's array, by row number, where the forward pass left the rest
-            if (GSEP && a.g_separate && e / BY == 1) src = reinterpret_cast<const uint32_t *>(a.g) + rows[LPW];
+            if (GSEP && a.g_separate && !a.g_stream_off && e / BY == 1) src = reinterpret_cast<const uint32_t *>(a.g) + rows[LPW];
             __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + OFF_C + inst * 128), 4, 0, 0);
         }
         if (ind) {
@@ -559,6 +605,28 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     run_s[g] = run_s[g] * __builtin_amdgcn_exp2f(run_m[g] - mn) + ((part[0] + part[1]) + (part[2] + part[3]));
                     run_m[g] = mn;
                 }
+            }
+        } else if (MODE == MODE_FDH) {
+            // One pass for the forward sum and for the probabilities of the second product: 2^(o log2e - ref) against the
+            // block's reference (see the FDH notes at the streaming loop); the sum is kept in fp32 from the unrounded
+            // values, the second product takes them rounded to bf16, and the epilogue divides by the sum.
+#pragma unroll
+            for (int g = 0; g < XG; ++g) {
+                const float ref = -run_m[g];
+                float v[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) v[q] = __builtin_amdgcn_exp2f(fmaf(sv[g][q], kLog2e, ref));
+                if (RAGGED) {
+#pragma unroll
+                    for (int q = 0; q < 16; ++q)
+                        if ((q / 4) * 8 + (q % 4) >= rem) v[q] = 0.f;
+                }
+                float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int q = 0; q < 16; ++q) part[q & 3] += v[q];
+                run_s[g] += (part[0] + part[1]) + (part[2] + part[3]);
+#pragma unroll
+                for (int q = 0; q < 16; q += 2) gp[g][q / 2] = pack2(v[q], v[q + 1]);
             }
         } else {
             const float *yc = reinterpret_cast<const float *>(tile + OFF_C);
@@ -686,7 +754,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
     constexpr int NM_S = KK * XG;                 // matrix instructions of a score product
     constexpr int NM_P = BWD ? 2 * MBH * XG : 0;  // ... of a second product
     constexpr int N_TR = 4 * MBH;                 // transpose reads of a second product
-    constexpr int VALU_C = XG * (MODE == MODE_FWD ? 56 : (MODE == MODE_DH ? 42 : 58));  // vector instructions of a softmax
+    constexpr int VALU_C = XG * (MODE == MODE_FWD ? 56 : (MODE == MODE_DH ? 42 : 58));  // vector instructions of a softmax (FDH: 58)
     auto process_tile = [&](int64_t t, const uint16_t *tile, auto ragged_tag, auto max_tag) {
         // rows of this tile that exist; only the last tile of the streamed range can be short
         const int rows_here = (n_y - t * BY < BY) ? (int)(n_y - t * BY) : BY;
@@ -753,7 +821,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             constexpr int BS = (DS == 1 && BWD) ? 2 : 4;  // operands per batch: two where all output columns are held
             // operand batches in flight: three in the dH pass (measured 2 % faster at d = 256), two elsewhere (in the dE
             // pass the third costs spilled registers and 7 %)
-            constexpr int RD = (DS == 1 && MODE == MODE_DH) ? 3 : 2;
+            constexpr int RD = (DS == 1 && (MODE == MODE_DH || MODE == MODE_FDH)) ? 3 : 2;
             constexpr int NB_S = KK / BS;         // batches of the score product
             constexpr int NB_P = 2 * MBH / BS;    // batches of the second product
             static_assert(KK % BS == 0 && MBH % BS == 0, "whole operand batches");
@@ -857,86 +925,216 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
 #pragma unroll
             for (int g = 0; g < XG; ++g) asm volatile("" : "+v"(run_m[g]), "+v"(run_s[g]));
         }
-    };
-    auto step = [&](int64_t t, const uint16_t *cur, uint16_t *nxt) {
-        if (t + PF < t_end) {
-            int32_t rows[NR];
-            rows_from_lds(t + PF, cur, rows);
-            issue_group(t + PF, rows, nxt);
+        if (MODE == MODE_FDH) {
+#pragma unroll
+            for (int g = 0; g < XG; ++g) asm volatile("" : "+v"(run_s[g]));
         }
-        // d = 256: few tiles per block and a kernel at the edge of its register budget; measured slower there
-        if (MODE == MODE_FWD && D <= 128 && t != t_begin) {  // the first tile has no maximum to lean on
-            float m0[XG], s0[XG];
-            bool over = false;
+    };
+    // ---- FDH: forward sum and hidden-state gradient in one pass (an online softmax, Alg. 1, carried through Eq. 6 left).
+    // The probabilities of the second product are taken against a reference m per position instead of the final
+    // log-sum-exp: acc = sum_j 2^(o_j log2e - m) E_j, run_s = sum_j 2^(o_j log2e - m), and the epilogue divides.  Any m
+    // gives the same result as long as nothing leaves the float range, so the fast attempt takes m = the largest score
+    // among the first 32 candidates of the block's range and never looks at a maximum again (no maximum chain, no
+    // rescaling, no branch inside the software-pipelined loop).  Scores that outgrow that reference by more than about
+    // 69 nats push a sum beyond 1e30: the wavefront that sees it raises a flag in LDS, every wavefront of the block reads
+    // the flag of the previous tile during a step (two flags, by tile parity, so that all of them read the same
+    // value), and the block starts over in the exact form: the largest score of every tile is taken first (a score
+    // product of its own), sums and accumulators are rescaled when it grows, and no exponent is ever positive.
+    int *const over_flag = reinterpret_cast<int *>(epi_own);
+    auto tile_max = [&](const uint16_t *tile, int nsub, int rows_here, float (&tmax)[XG]) {
 #pragma unroll
-            for (int g = 0; g < XG; ++g) {
-                m0[g] = run_m[g];
-                s0[g] = run_s[g];
-            }
-            process_tile(t, cur, Full{}, Lazy{});
+        for (int g = 0; g < XG; ++g) tmax[g] = -INFINITY;
+#pragma unroll 1
+        for (int sb = 0; sb < nsub; ++sb) {
+            f32x16 sv[XG];
 #pragma unroll
-            for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 1.0e30f);  // near overflow (or NaN): the merges of
-                                                                              // half-waves and of split runs add up to 16 such sums
-            if (__any(over)) {
+            for (int g = 0; g < XG; ++g)
+#pragma unroll
+                for (int q = 0; q < 16; ++q) sv[g][q] = 0.f;
+            const uint16_t *arow = tile + sb * 32 * D;
+#pragma unroll
+            for (int kk = 0; kk < KK; kk += 2) {  // two operands at a time: registers are short at large hidden sizes
+                const uint4 o0 = *reinterpret_cast<const uint4 *>(lds_at(arow, a_base, ((kk * 2) & SM) * 8, (kk / NA) * (NA * 16)));
+                const uint4 o1 = *reinterpret_cast<const uint4 *>(lds_at(arow, a_base, (((kk + 1) * 2) & SM) * 8, ((kk + 1) / NA) * (NA * 16)));
 #pragma unroll
                 for (int g = 0; g < XG; ++g) {
-                    run_m[g] = m0[g];
-                    run_s[g] = s0[g];
+                    sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(o0), as_bf16x8(xr[g][kk]), sv[g], 0, 0, 0);
+                    sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(o1), as_bf16x8(xr[g][kk + 1]), sv[g], 0, 0, 0);
                 }
+            }
+            const int rem = rows_here - sb * 32 - hi * 4;
+#pragma unroll
+            for (int g = 0; g < XG; ++g) {
+                float tm = -INFINITY;
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if ((q / 4) * 8 + (q % 4) < rem) tm = fmaxf(tm, sv[g][q]);
+                tmax[g] = fmaxf(tmax[g], tm * kLog2e);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < XG; ++g) tmax[g] = fmaxf(tmax[g], __shfl_xor(tmax[g], 32, 64));  // both halves of a position agree
+    };
+    // Exact form: bring the reference up to the largest score of the tile at hand before its exponentials are taken.
+    auto raise_reference = [&](const uint16_t *tile, int rows_here) {
+        float tmax[XG];
+        tile_max(tile, NSB, rows_here, tmax);
+        bool grow = false;
+#pragma unroll
+        for (int g = 0; g < XG; ++g) grow |= tmax[g] > run_m[g];
+        if (__any(grow)) {
+#pragma unroll
+            for (int g = 0; g < XG; ++g) {
+                const float mn = fmaxf(run_m[g], tmax[g]);
+                const float sc = (mn == run_m[g]) ? 1.f : __builtin_amdgcn_exp2f(run_m[g] - mn);  // first tile: 2^-inf = 0
+                run_m[g] = mn;
+                run_s[g] *= sc;
+#pragma unroll
+                for (int mb = 0; mb < (MODE == MODE_FWD ? 1 : MBH); ++mb)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[g][mb][q] *= sc;
+            }
+        }
+    };
+    auto note_overflow = [&](int parity) {
+        bool over = false;
+#pragma unroll
+        for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 1.0e30f);  // or NaN
+        if (__any(over) && lane == 0) over_flag[parity] = 1;
+    };
+    // One attempt at the streamed range: prologue loads, the ring of steps, the short last tile.  Returns whether the
+    // block has to start over (FDH, fast form only; the value is the same in every wavefront of the block).
+    auto run_attempt = [&](auto form) -> bool {
+        constexpr bool EXACT = decltype(form)::exact;
+        constexpr bool WATCH = (MODE == MODE_FDH) && !EXACT;  // the fast form watches for sums that leave the float range
+        int overflow = 0;  // wave-uniform
+        auto step = [&](int64_t t, const uint16_t *cur, uint16_t *nxt) {
+            if (t + PF < t_end) {
+                int32_t rows[NR];
+                rows_from_lds(t + PF, cur, rows);
+                issue_group(t + PF, rows, nxt);
+            }
+            if (MODE == MODE_FDH && EXACT) raise_reference(cur, BY);
+            // The flag that the previous step may have raised (every wavefront of the block reads it between the same
+            // two barriers, so all of them see the same value); the read lands under the work on this tile.
+            int seen = 0;
+            if (WATCH && t != t_begin) seen = over_flag[(int)((t - t_begin - 1) & 1)];
+            // d = 256: few tiles per block and a kernel at the edge of its register budget; measured slower there
+            if (MODE == MODE_FWD && D <= 128 && t != t_begin) {  // the first tile has no maximum to lean on
+                float m0[XG], s0[XG];
+                bool over = false;
+#pragma unroll
+                for (int g = 0; g < XG; ++g) {
+                    m0[g] = run_m[g];
+                    s0[g] = run_s[g];
+                }
+                process_tile(t, cur, Full{}, Lazy{});
+#pragma unroll
+                for (int g = 0; g < XG; ++g) over |= !(run_s[g] < 1.0e30f);  // near overflow (or NaN): the merges of
+                                                                                  // half-waves and of split runs add up to 16 such sums
+                if (__any(over)) {
+#pragma unroll
+                    for (int g = 0; g < XG; ++g) {
+                        run_m[g] = m0[g];
+                        run_s[g] = s0[g];
+                    }
+                    process_tile(t, cur, Full{}, Exact{});
+                }
+            } else {
                 process_tile(t, cur, Full{}, Exact{});
             }
-        } else {
-            process_tile(t, cur, Full{}, Exact{});
+            pin_results();
+            if (WATCH) {
+                note_overflow((int)((t - t_begin) & 1));
+                overflow |= __builtin_amdgcn_readfirstlane(seen);
+            }
+            wait_for_next(t);
+            barrier_keep_loads();
+        };
+        if (WATCH && tid < 2) over_flag[tid] = 0;  // visible behind the barrier that follows the first loads
+        if (t_begin < t_end) {
+            int32_t rows[PF][NR];
+#pragma unroll
+            for (int j = 0; j < PF; ++j)
+                if (t_begin + j < t_end) rows_from_global(t_begin + j, rows[j]);
+#pragma unroll
+            for (int j = 0; j < PF; ++j)
+                if (t_begin + j < t_end) issue_group(t_begin + j, rows[j], buf_at(j));
         }
-        pin_results();
-        wait_for_next(t);
+        wait_for_next(t_begin - 1);
         barrier_keep_loads();
+        if (WATCH && t_begin < t_end) {  // reference of the fast form: the largest score among the first 32 candidates
+            const int64_t left = n_y - t_begin * BY;
+            float tmax[XG];
+            tile_max(buf_at(0), 1, left < BY ? (int)left : BY, tmax);
+#pragma unroll
+            for (int g = 0; g < XG; ++g) run_m[g] = tmax[g];
+        }
+        if (NBUF == 4) {
+            for (int64_t t = t_begin; t < t_stop; t += 4) {
+                step(t, buf0, buf3);
+                if (t + 1 >= t_stop || overflow) break;
+                step(t + 1, buf1, buf0);
+                if (t + 2 >= t_stop || overflow) break;
+                step(t + 2, buf2, buf1);
+                if (t + 3 >= t_stop || overflow) break;
+                step(t + 3, buf3, buf2);
+                if (overflow) break;
+            }
+        } else if (NBUF == 3) {
+            for (int64_t t = t_begin; t < t_stop; t += 3) {
+                step(t, buf0, buf2);
+                if (t + 1 >= t_stop || overflow) break;
+                step(t + 1, buf1, buf0);
+                if (t + 2 >= t_stop || overflow) break;
+                step(t + 2, buf2, buf1);
+                if (overflow) break;
+            }
+        } else if (NBUF == 2) {
+            for (int64_t t = t_begin; t < t_stop; t += 2) {
+                step(t, buf0, buf1);
+                if (t + 1 >= t_stop || overflow) break;
+                step(t + 1, buf1, buf0);
+                if (overflow) break;
+            }
+        } else {
+            for (int64_t t = t_begin; t < t_stop && !overflow; ++t) {
+                const int s = (int)((t - t_begin) & 1);
+                step(t, buf_at(s), buf_at(s ^ 1));
+            }
+        }
+        if (tail_ragged && !overflow) {  // its group was issued with the others, and the last wait above was for all loads
+            const uint16_t *last = buf_at((int)((t_stop - t_begin) % NB));
+            if (MODE == MODE_FDH && EXACT) raise_reference(last, (int)(n_y - t_stop * BY));
+            process_tile(t_stop, last, Ragged{}, Exact{});
+            if (WATCH) note_overflow(0);
+            __syncthreads();  // the dE epilogue reuses the tile buffers
+        }
+        if (WATCH) {
+            // the flags of the last step and of the short tile have not been read yet (the last barrier is behind us)
+            if (!overflow) overflow = __builtin_amdgcn_readfirstlane(over_flag[0] | over_flag[1]);
+            if (overflow) {  // loads of later tiles may still be in flight into the ring: let them land
+                wait_vm<0>();
+                __syncthreads();
+            }
+        }
+        return overflow != 0;
     };
-    if (t_begin < t_end) {
-        int32_t rows[PF][NR];
+    if (run_attempt(FastTag{})) {
+        if constexpr (MODE == MODE_FDH) {  // start over in the exact form
 #pragma unroll
-        for (int j = 0; j < PF; ++j)
-            if (t_begin + j < t_end) rows_from_global(t_begin + j, rows[j]);
+            for (int g = 0; g < XG; ++g) {
+                run_m[g] = -INFINITY;
+                run_s[g] = 0.f;
 #pragma unroll
-        for (int j = 0; j < PF; ++j)
-            if (t_begin + j < t_end) issue_group(t_begin + j, rows[j], buf_at(j));
-    }
-    wait_for_next(t_begin - 1);
-    barrier_keep_loads();
-    if (NBUF == 4) {
-        for (int64_t t = t_begin; t < t_stop; t += 4) {
-            step(t, buf0, buf3);
-            if (t + 1 >= t_stop) break;
-            step(t + 1, buf1, buf0);
-            if (t + 2 >= t_stop) break;
-            step(t + 2, buf2, buf1);
-            if (t + 3 >= t_stop) break;
-            step(t + 3, buf3, buf2);
-        }
-    } else if (NBUF == 3) {
-        for (int64_t t = t_begin; t < t_stop; t += 3) {
-            step(t, buf0, buf2);
-            if (t + 1 >= t_stop) break;
-            step(t + 1, buf1, buf0);
-            if (t + 2 >= t_stop) break;
-            step(t + 2, buf2, buf1);
-        }
-    } else if (NBUF == 2) {
-        for (int64_t t = t_begin; t < t_stop; t += 2) {
-            step(t, buf0, buf1);
-            if (t + 1 >= t_stop) break;
-            step(t + 1, buf1, buf0);
-        }
-    } else {
-        for (int64_t t = t_begin; t < t_stop; ++t) {
-            const int s = (int)((t - t_begin) & 1);
-            step(t, buf_at(s), buf_at(s ^ 1));
+                for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) acc[g][mb][q] = 0.f;
+            }
+            run_attempt(ExactTag{});
         }
     }
-    if (tail_ragged) {  // its group was issued with the others, and the last wait above was for all loads
-        process_tile(t_stop, buf_at((int)((t_stop - t_begin) % NB)), Ragged{}, Exact{});
-        __syncthreads();  // the dE epilogue reuses the tile buffers
-    }
+
 
     // =====================================================================================================  epilogues
     if (MODE == MODE_FWD) {
@@ -976,6 +1174,60 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 const float nl = -l * kLog2e;
                 a.coef[xrow[g]] = w * __builtin_amdgcn_exp2f(fmaf(op, kLog2e, nl)) - 1.f;
                 a.de_const[x] = __float_as_uint(nl);
+            }
+        }
+    } else if (MODE == MODE_FDH) {
+#pragma unroll
+        for (int g = 0; g < XG; ++g) {
+            const int64_t x = xb * XPB + (xgrp * XG + g) * 32 + lo;
+            const float rm = run_m[g];
+            const float rs = run_s[g] + __shfl_xor(run_s[g], 32, 64);  // the two halves share the reference
+            if (splits > 1) {  // partial (reference, sum, rows) of this part of the candidate range; the merge finishes
+                if (x_ok[g]) {
+                    const int64_t slot = (int64_t)split * part_rows + (x - part_x0);
+                    if (hi == 0 && half == 0) {
+                        a.part_m[slot] = rm;
+                        a.part_s[slot] = rs;
+                    }
+                    float *dst = a.part_dH + slot * D;
+#pragma unroll
+                    for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+                        for (int qq = 0; qq < 4; ++qq)
+                            *reinterpret_cast<float4 *>(dst + (half * MBH + mb) * 32 + qq * 8 + hi * 4) = make_float4(
+                                acc[g][mb][qq * 4], acc[g][mb][qq * 4 + 1], acc[g][mb][qq * 4 + 2], acc[g][mb][qq * 4 + 3]);
+                }
+                continue;
+            }
+            float op = 0.f;
+            const uint16_t *erow = a.E + (x_ok[g] ? (int64_t)a.tgt[xrow[g]] : 0) * D;
+            if (x_ok[g]) op = half_row_dot<D>(xr[g], erow, hi);
+            op += __shfl_xor(op, 32, 64);
+            if (x_ok[g]) {
+                const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[xrow[g]] : 1.f);
+                const float o2 = op * kLog2e;
+                const float M = (w != 0.f) ? fmaxf(rm, o2) : rm;
+                const float e1 = __builtin_amdgcn_exp2f(rm - M), e2 = (w != 0.f) ? w * __builtin_amdgcn_exp2f(o2 - M) : 0.f;
+                const float tot = rs * e1 + e2;
+                const float l = (M + __builtin_amdgcn_logf(tot)) * kLn2;
+                const float inv = e1 / tot;        // 2^(reference) / sum of all live exponentials
+                const float cpos = e2 / tot - 1.f;  // coefficient of the correct item, w p+ - 1
+                if (hi == 0 && half == 0) {
+                    a.lse[xrow[g]] = l;
+                    a.loss[xrow[g]] = l - op;
+                    a.coef[xrow[g]] = cpos;
+                    a.de_const[x] = __float_as_uint(-l * kLog2e);
+                }
+#pragma unroll
+                for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+                    for (int qq = 0; qq < 4; ++qq) {
+                        const int col = (half * MBH + mb) * 32 + qq * 8 + hi * 4;
+                        const uint2 ev = *reinterpret_cast<const uint2 *>(erow + col);
+                        *reinterpret_cast<float4 *>(a.U + xrow[g] * D + col) =
+                            make_float4(fmaf(cpos, bf16_lo(ev.x), acc[g][mb][qq * 4 + 0] * inv), fmaf(cpos, bf16_hi(ev.x), acc[g][mb][qq * 4 + 1] * inv),
+                                        fmaf(cpos, bf16_lo(ev.y), acc[g][mb][qq * 4 + 2] * inv), fmaf(cpos, bf16_hi(ev.y), acc[g][mb][qq * 4 + 3] * inv));
+                    }
             }
         }
     } else if (MODE == MODE_DH) {
@@ -1235,6 +1487,85 @@ __global__ __launch_bounds__(256) void dh_merge_kernel(TileArgs a)
     }
 }
 
+// Merge of a split FDH pass: the parts of a position's candidate range come with their own reference m_s, sum l_s and
+// unnormalised rows A_s; with M = max m_s the position's sum is sum_s l_s 2^(m_s - M) and its rows sum_s A_s 2^(m_s - M).
+// Then as in the unsplit epilogue: the correct item's term, lse, loss, the constants of the backward pass, and U.
+template <int D, int TAIL_XPB = 0>
+__global__ __launch_bounds__(256) void fdh_merge_kernel(TileArgs a)
+{
+    constexpr int LPR = D / 8;  // lanes per position, 8 columns each
+    static_assert(64 % LPR == 0, "a row must not straddle wavefronts");
+    constexpr int PPB = 256 / LPR;
+    const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
+    int64_t x = (int64_t)blockIdx.x * PPB + threadIdx.x / LPR;
+    int64_t part_rows = a.N, part_x0 = 0;
+    int splits = a.splits;
+    if constexpr (TAIL_XPB > 0) {
+        const TailPlan tp = tail_plan((n_pos + TAIL_XPB - 1) / TAIL_XPB, a.tail_slots);
+        part_rows = tp.tail * TAIL_XPB;
+        part_x0 = tp.whole * TAIL_XPB;
+        splits = tp.splits;
+        if (x >= part_rows) x = n_pos;  // nothing to merge here
+        else x += part_x0;
+    }
+    const int c = threadIdx.x % LPR;
+    const bool ok = x < n_pos;
+    const int64_t row = ok ? pos_row(a, x) : 0;
+    float h[8], e[8], sum[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) h[t] = e[t] = sum[t] = 0.f;
+    float op = 0.f, M = -INFINITY, l = 0.f;
+    if (ok) {
+        load8(a.H + row * D + c * 8, h);
+        load8(a.E + (int64_t)a.tgt[row] * D + c * 8, e);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) op = fmaf(h[t], e[t], op);
+        for (int sp = 0; sp < splits; ++sp) M = fmaxf(M, a.part_m[(int64_t)sp * part_rows + (x - part_x0)]);
+        for (int sp = 0; sp < splits; ++sp) {
+            const int64_t slot = (int64_t)sp * part_rows + (x - part_x0);
+            const float ms = a.part_m[slot];
+            if (ms == -INFINITY) continue;  // a part without candidates
+            const float sc = __builtin_amdgcn_exp2f(ms - M);
+            l = fmaf(a.part_s[slot], sc, l);
+            float v[8];
+            load8(a.part_dH + slot * D + c * 8, v);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum[t] = fmaf(v[t], sc, sum[t]);
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) op += __shfl_xor(op, off, 64);
+    if (ok) {
+        const float w = a.pos_weight_mode == 2 ? 0.f : (a.cnt ? 1.f - (float)a.cnt[row] : 1.f);
+        const float o2 = op * kLog2e;
+        const float Mx = (w != 0.f) ? fmaxf(M, o2) : M;
+        const float e1 = __builtin_amdgcn_exp2f(M - Mx), e2 = (w != 0.f) ? w * __builtin_amdgcn_exp2f(o2 - Mx) : 0.f;
+        const float tot = l * e1 + e2;
+        const float lse = (Mx + __builtin_amdgcn_logf(tot)) * kLn2;
+        const float inv = e1 / tot, cpos = e2 / tot - 1.f;
+        if (c == 0) {
+            a.lse[row] = lse;
+            a.loss[row] = lse - op;
+            a.coef[row] = cpos;
+            a.de_const[x] = __float_as_uint(-lse * kLog2e);
+        }
+        float4 *out = reinterpret_cast<float4 *>(a.U + row * D + c * 8);
+        out[0] = make_float4(fmaf(cpos, e[0], sum[0] * inv), fmaf(cpos, e[1], sum[1] * inv), fmaf(cpos, e[2], sum[2] * inv), fmaf(cpos, e[3], sum[3] * inv));
+        out[1] = make_float4(fmaf(cpos, e[4], sum[4] * inv), fmaf(cpos, e[5], sum[5] * inv), fmaf(cpos, e[6], sum[6] * inv), fmaf(cpos, e[7], sum[7] * inv));
+    }
+}
+
+template <int D, bool FILE_G>
+__global__ __launch_bounds__(256) void dh_scale_kernel(TileArgs a)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (FILE_G) {
+        const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
+        if (chunk < n_pos) a.de_const[a.N + chunk] = __float_as_uint(a.g ? a.g[pos_row(a, chunk)] : 1.f);
+    }
+    dh_scale_chunk<D>(a, chunk);
+}
+
 // ---------------------------------------------------------------------------------------------------------------------
 // Blocks of one kernel instantiation that the current device holds at once.  The answer is cached per instantiation
 // (the template makes the static array one per kernel) and per device ordinal.
@@ -1307,6 +1638,11 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
         a.pad_blocks = (a.pos_mask || a.validate) ? (a.N + threads - 1) / threads : 0;
         blocks += a.pad_blocks;
     }
+    if (MODE == MODE_DE && a.scale_blocks > 0) {  // wanted by the caller: dH = grad_loss * U in trailing blocks
+        a.scale_block0 = blocks;
+        a.scale_blocks = (a.N * (a.d / 8) + (int64_t)threads * kScaleChunks - 1) / ((int64_t)threads * kScaleChunks);
+        blocks += a.scale_blocks;
+    }
     return blocks;
 }
 
@@ -1318,11 +1654,11 @@ hipError_t launch_tile_kernel(TileArgs &a, int64_t n_x, hipStream_t stream)
     int64_t blocks = plan_tile_grid<MODE>(a, n_x, XPB, NW * 64, slots);
     if (blocks == 0) return hipSuccess;
     a.tail_slots = 0;
-    if (MODE == MODE_DH && D > 128 && a.splits == 1 && n_x > kTailRows && (int64_t)slots * XPB <= kTailRows) {
+    if ((MODE == MODE_DH || MODE == MODE_FDH) && D > 128 && a.splits == 1 && n_x > kTailRows && (int64_t)slots * XPB <= kTailRows) {
         a.tail_slots = slots;  // last-round split: at most `slots` blocks more than position blocks
         blocks += slots;
     }
-    ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : PROF_TILE_DE), stream);
+    ProfScope prof(MODE == MODE_FWD ? PROF_TILE_FWD : (MODE == MODE_DH ? PROF_TILE_DH : (MODE == MODE_DE ? PROF_TILE_DE : PROF_TILE_FDH)), stream);
     hipLaunchKernelGGL((tile_kernel<D, MODE, BY, NW, XG, MINB, NBUF, DS, FILTER>), dim3((unsigned)blocks), dim3(NW * 64), 0, stream, a);
     return hipGetLastError();
 }
@@ -1419,6 +1755,32 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
         }
         return e;
     }
+    case TILE_PASS_FDH: {  // the dH pass's shapes: same stationary rows, same splits, same last-round plan
+        bool done = false;
+        if constexpr (XG_B == 2) {
+            if (wide(a.N, true)) {
+                e = launch_tile_kernel<D, MODE_FDH, BY_B, 4, 2, MINB, NBUF_B>(a, a.N, stream);
+                done = true;
+            }
+        }
+        if (!done) e = launch_tile_kernel<D, MODE_FDH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
+        if constexpr (D > 128) {
+            if (e == hipSuccess && a.tail_slots > 0) {
+                constexpr int PPB = 256 / (D / 8), XPB_L = NW_L * 32;
+                const int64_t rows = (int64_t)(a.tail_slots / 2) * XPB_L;
+                ProfScope prof(PROF_FDH_MERGE, stream);
+                hipLaunchKernelGGL((fdh_merge_kernel<D, XPB_L>), dim3((unsigned)((rows + PPB - 1) / PPB)), dim3(256), 0, stream, a);
+                e = hipGetLastError();
+            }
+        }
+        if (e == hipSuccess && a.splits > 1) {
+            constexpr int PPB = 256 / (D / 8);
+            ProfScope prof(PROF_FDH_MERGE, stream);
+            hipLaunchKernelGGL((fdh_merge_kernel<D>), dim3((unsigned)((a.N + PPB - 1) / PPB)), dim3(256), 0, stream, a);
+            e = hipGetLastError();
+        }
+        return e;
+    }
     case TILE_PASS_DE:
         if constexpr (D > 128) {
             // One block of eight wavefronts per compute unit: scatter blocks at the head of this launch would run 256
@@ -1485,6 +1847,17 @@ __global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
 {
     __shared__ uint64_t keys[kPosChunk];
     pos_scatter_block<D>(a, blockIdx.x, keys);
+}
+
+template <int D>
+hipError_t launch_dh_scale_d(const TileArgs &a, bool file_g, hipStream_t stream)
+{
+    if (a.N == 0) return hipSuccess;
+    const dim3 grid((unsigned)((a.N * (D / 8) + 255) / 256)), block(256);
+    ProfScope prof(PROF_DH_SCALE, stream);
+    if (file_g) hipLaunchKernelGGL((dh_scale_kernel<D, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((dh_scale_kernel<D, false>), grid, block, 0, stream, a);
+    return hipGetLastError();
 }
 
 template <int D>

@@ -9,5 +9,6 @@ hipError_t launch_tile_backward_d64(const TileArgs &a_dh, const TileArgs &a_de, 
     return launch_bwd_for_d<64>(a_dh, a_de, stream);
 }
 hipError_t launch_pos_scatter_d64(const TileArgs &a, hipStream_t stream) { return launch_pos_scatter_d<64>(a, stream); }
+hipError_t launch_dh_scale_d64(const TileArgs &a, bool file_g, hipStream_t stream) { return launch_dh_scale_d<64>(a, file_g, stream); }
 
 }  // namespace cce

@@ -28,16 +28,18 @@ def to_device(w):
 
 def run_hip(w, *, g: Optional[np.ndarray] = "workload", algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32, validate=0,
             use_mask=True, dE_init: Optional[np.ndarray] = None, repeat_backward: int = 1, reuse_prep: bool = False,
-            filter_eps: float = 0.0):
+            filter_eps: float = 0.0, fuse_dH: bool = False):
     """Forward + backward on cuda:0.  Returns dict(loss, lse, dH (float32), dE (float32), status)."""
     H, E, tgt, neg, mask = to_device(w)
     if not use_mask:
         mask = None
     desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
-                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate, algo=algo)
+                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate, algo=algo,
+                       fuse_dH=1 if fuse_dH else 0)
     desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
                            dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, validate_indices=validate,
-                           algo=algo, reuse_forward_prep=1 if reuse_prep else 0, filter_eps=filter_eps)
+                           algo=algo, reuse_forward_prep=1 if reuse_prep else 0, filter_eps=filter_eps,
+                           fuse_dH=1 if fuse_dH else 0)
     ws = P.new_workspace(desc)
     loss = torch.full((w.N,), float("nan"), device="cuda")
     lse = torch.full((w.N,), float("nan"), device="cuda")
