@@ -110,9 +110,13 @@ typedef struct {
  *                              of at most 40,960 positions, 4 d bytes per position and dH split; hidden size 256 and
  *                              more than 65,536 positions: 64 MiB of partial dH rows for the split of the last round
  *                              of blocks;
- *   per-position mode:         12 bytes per (position, negative) pair for the inverted index that turns the dE
- *                              scatter into a gather (pairs sorted by item) and 1/8 byte per pair for the work
- *                              list of items sampled very often, 4 bytes per table row, 4 per position;
+ *   per-position mode:         the inverted index that turns the dE scatter into a gather (pairs sorted by item) is
+ *                              built and used up in slices of the item-id range: 12 1/8 bytes per pair of ONE slice,
+ *                              a slice holding at most B = max(2^22, N K / 8) pairs (so at most 51 MB up to
+ *                              N K = 2^25 pairs, and 3/8 of the bytes of the [N,K] id matrix itself beyond), plus
+ *                              4 bytes per table row, 4 per position and at most 32 MiB of bucket counts.  Catalogues
+ *                              of more than 2^22 items whose pairs exceed B: a 256-byte header (they keep the atomic
+ *                              row adds of Alg. 2);
  *   otherwise:                 a 256-byte header;
  *   shared mode, in addition:  4 bytes per negative (where the *_sampled calls write the list they draw).
  * No score, probability or gradient-coefficient matrix is ever stored: the workspace holds indices and per-position
@@ -181,7 +185,8 @@ cce_status cce_neg_forward_noalloc(const cce_desc *desc, const void *H, const vo
  * or popularity-based sampling through a multinomial over the catalogue: Sec. 5, "Comparison Sampling Strategies")
  * and names the stored index matrix as the memory cost of CCE- over CCE (Sec. 5, "What is better").  The *_sampled
  * calls take a sampler instead of `neg`: every id is a pure function of (seed, stream, position, slot), recomputed
- * wherever the kernels need it, so the [N,K] matrix is never stored.
+ * wherever the kernels need it, so the [N,K] matrix is never stored (the backward call's inverted index holds one
+ * slice of (item, position) pairs at a time, see cce_neg_workspace_bytes).
  *   generator  Philox4x32-10 (Salmon et al., SC'11), key = (seed low word, seed high word),
  *              counter = (q, position low word, position high word, stream)
  *   slot s (0 <= s < K) of position i is draw j = s + 1

@@ -41,7 +41,7 @@ class _CceNegLoss(torch.autograd.Function):
         dt = B.CCE_F32 if H.dtype == torch.float32 else B.CCE_BF16
         # fuse_dH: the forward call also forms the hidden-state gradient short of grad_loss (one pass over the candidates
         # less per step); only worth it when a backward call will follow, and not with gradient filtering
-        fuse = 1 if ((H.requires_grad or E.requires_grad) and not filter_eps > 0) else 0
+        fuse = 1 if ((ctx.needs_input_grad[0] or ctx.needs_input_grad[1]) and not filter_eps > 0) else 0
         kw = dict(dH_dtype=dt, mask_target_collisions=1 if mask_target_collisions else 0, fuse_dH=fuse)
         desc = B.make_desc(N, V, d, K, dt, neg_mode, **kw)
         B.check_step_args(desc, H, E, tgt, neg, mask, sampled=sampler is not None)   # before anything touches the device

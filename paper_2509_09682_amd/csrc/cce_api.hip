@@ -150,17 +150,19 @@ Params make_params(const cce_desc *d, const void *H, const void *E, const int32_
     return p;
 }
 
-// Workspace of the per-position mode: the correct-item coefficients and the inverted index of the negatives
-// (4 bytes per (position, negative) pair, as large as the `neg` input itself, plus one word per item).
+// Workspace of the per-position mode: the correct-item coefficients and the inverted index of the negatives, which is
+// built and used up in slices of the item-id range: 12 bytes per pair of ONE slice (at most max(2^22, N K / 8) pairs),
+// one word per item, one per position, and the (bucket, block) counts of the first sort level (32 MiB at most).
 struct PpLayout {
-    size_t coef, cursor, block_sums, pairs, tmp, part_hist, hot_list, total;
+    size_t coef, cursor, block_sums, pairs, tmp, part_hist, hot_list, plan, total;
 };
 PpLayout make_pp_layout(const cce_desc *d)
 {
     PpLayout L{};
-    const size_t n_pairs = (size_t)d->N * (size_t)d->K;
+    const size_t n_pairs = (size_t)invert_index_pairs(d->N, d->K);
     const bool part = invert_partitioned(d->V);
-    const size_t n_hist = part ? (size_t)invert_buckets(d->V) * (size_t)invert_part_blocks(d->N, d->K) + 1 : 0;
+    const size_t n_buckets = part ? (size_t)invert_buckets(d->V) : 0;
+    const size_t n_hist = part ? n_buckets * (size_t)invert_part_blocks(d->N, d->K) + 1 : 0;
     const size_t scan_n = part ? n_hist : (size_t)d->V;
     size_t off = kHeaderBytes;
     L.coef = off;        off += align256((size_t)d->N * 4);
@@ -170,13 +172,16 @@ PpLayout make_pp_layout(const cce_desc *d)
     L.tmp = off;         off += part ? align256(n_pairs * 8) : 0;
     L.part_hist = off;   off += align256(n_hist * 4);
     L.hot_list = off;    off += align256(invert_hot_capacity(d->N, d->K) * 16);
+    L.plan = off;        off += align256((2 * n_buckets + (size_t)invert_plan_words()) * 4);
     L.total = off;
     return L;
 }
 bool use_inverted(const cce_desc *d)
 {
-    // the index holds 32-bit offsets: larger problems keep the atomic row adds of the row-gather pass
-    return d->neg_mode == CCE_NEG_PER_POSITION && d->K > 0 && d->N * (int64_t)d->K < 0x7fffffffLL;
+    // The index holds 32-bit offsets: larger problems keep the atomic row adds of the row-gather pass, and so do
+    // catalogues beyond the sliced build (more than 2048 * 2048 items) whose pairs do not fit one slice.
+    if (d->neg_mode != CCE_NEG_PER_POSITION || d->K <= 0 || d->N * (int64_t)d->K >= 0x7fffffffLL) return false;
+    return invert_partitioned(d->V) || invert_slices(d->N, d->K) == 1;
 }
 
 TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const void *E, const int32_t *tgt,
@@ -512,6 +517,10 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
     ia.tmp = reinterpret_cast<int2 *>(ws + L.tmp);
     ia.part_hist = reinterpret_cast<int32_t *>(ws + L.part_hist);
     ia.hot_list = reinterpret_cast<int4 *>(ws + L.hot_list);
+    ia.bucket_start = reinterpret_cast<int32_t *>(ws + L.plan);
+    const int64_t n_buckets = cce::invert_partitioned(desc->V) ? cce::invert_buckets(desc->V) : 0;
+    ia.slice_of = ia.bucket_start + n_buckets;
+    ia.slice_hot = ia.slice_of + n_buckets;
     ia.hot_count = static_cast<int32_t *>(workspace) + cce::kHdrHot;
     ia.hot_capacity = (int32_t)cce::invert_hot_capacity(desc->N, desc->K);
     ia.N = desc->N;

@@ -134,7 +134,20 @@ __global__ __launch_bounds__(kThreads) void fill_kernel(InvertArgs a)
 constexpr int kBucketShift = 11;
 constexpr int kBucketIds = 1 << kBucketShift;  // LDS histogram of level 2: 8 KiB
 constexpr int kMaxBuckets = 2048;               // LDS histogram of level 1: 8 KiB
-constexpr int kChunkPairs = 8192;               // pairs per block in level 1
+constexpr int kChunkPairs = 8192;               // pairs per chunk in level 1; a block takes chunks blockIdx.x, + gridDim.x, ...
+constexpr int kMaxPartBlocks = 4096;            // blocks of level 1: bounds the (bucket, block) histogram at 32 MiB
+// The index is built and used up in SLICES of the item-id range, so that its memory is bounded by a pair budget B instead
+// of growing with N * K: every slice is a run of consecutive buckets that holds at most B pairs, gets filed into the same
+// B-entry arrays, and is consumed by the item pass before the next one is filed.  Every table row is still read and
+// written once; a further slice costs one more reading of the ids (4 bytes per pair) and four launches.
+//   B = max(2^22, N K / 8) pairs;  slices = 1 if N K <= B, else ceil(N K / (7/8 B)): the pairs of the ordinary buckets
+//   are cut at the quantiles j / slices of their running count, so a slice holds at most N K / slices + (one bucket)
+//   <= 7/8 B + 1/8 B pairs, PROVIDED no bucket holds more than B / 8 pairs.  Buckets beyond that (2048 consecutive ids
+//   drawing more than half a million pairs, an eighth of everything: a popularity law far more skewed than any workload
+//   here) stay out of the index: their pairs are added to dE one by one with atomics (hot_bucket_kernel).
+constexpr int64_t kMinPairBudget = int64_t(1) << 22;
+constexpr int kMaxSlices = 32;
+constexpr int kSliceHot = -1;                   // slice_of[] of a bucket that stays out of the index
 
 // The pairs of a block's chunk, kPairBatch per thread at a time: all mask bytes are requested first, then ids and
 // targets of the valid positions only (entries of padded positions are never read), so a thread waits for two round
@@ -179,12 +192,72 @@ __global__ __launch_bounds__(kThreads) void part_count_kernel(InvertArgs a)
     __shared__ int32_t hist[kMaxBuckets];
     for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) hist[b] = 0;
     __syncthreads();
-    for_live_pairs(a, (int64_t)blockIdx.x, [&](int32_t id, int32_t) { atomicAdd(&hist[id >> kBucketShift], 1); });
+    for (int64_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x)
+        for_live_pairs(a, chunk, [&](int32_t id, int32_t) { atomicAdd(&hist[id >> kBucketShift], 1); });
     __syncthreads();
     for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) a.part_hist[(int64_t)b * gridDim.x + blockIdx.x] = hist[b];
-    if (blockIdx.x == 0 && threadIdx.x == 0) {  // two words the later kernels of this call expect to be zero
-        *a.part_total = 0;   // last entry of the scanned array: receives the grand total
-        *a.hot_count = 0;    // work list of the item pass
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.part_total = 0;  // last entry of the scanned array: receives the grand total
+}
+
+// Cuts the buckets into slices (see above) from the scanned (bucket, block) counts: slice_of[b], the start of every
+// bucket inside its slice's arrays, and the cleared work-list counters of the slices.  One block.
+__global__ __launch_bounds__(kScanThreads) void plan_slices_kernel(InvertArgs a)
+{
+    __shared__ int32_t lds[kScanThreads / 64 + 1];
+    __shared__ int32_t base[kMaxSlices], lo[kMaxSlices], hi[kMaxSlices], any_hot;
+    constexpr int PER = kMaxBuckets / kScanThreads;
+    const int64_t nb = a.n_part_blocks;
+    int32_t cnt[PER], cum[PER], sum = 0;
+    bool hot[PER];
+    for (int j = threadIdx.x; j < kMaxSlices; j += kScanThreads) {
+        base[j] = lo[j] = 0x7fffffff;
+        hi[j] = -1;
+        a.slice_hot[j] = 0;
+    }
+    if (threadIdx.x == 0) any_hot = 0;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+        const int b = threadIdx.x * PER + t;
+        cnt[t] = 0;
+        if (b < a.n_buckets) {
+            const int32_t s0 = a.part_hist[(int64_t)b * nb];
+            const int32_t s1 = (b + 1 < a.n_buckets) ? a.part_hist[(int64_t)(b + 1) * nb] : a.part_total[0];
+            cnt[t] = s1 - s0;
+        }
+        hot[t] = a.n_slices > 1 && (int64_t)cnt[t] > a.budget / 8;
+        cum[t] = sum;                  // running count of the ordinary buckets in front of this one, within the thread
+        if (!hot[t]) sum += cnt[t];
+    }
+    int32_t total;
+    const int32_t before = block_exclusive_scan(sum, lds, total);
+    const int32_t per_slice = (total + a.n_slices - 1) / a.n_slices > 0 ? (total + a.n_slices - 1) / a.n_slices : 1;
+    int32_t sl[PER];
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+        cum[t] += before;
+        sl[t] = hot[t] ? kSliceHot : min(cum[t] / per_slice, a.n_slices - 1);
+        const int b = threadIdx.x * PER + t;
+        if (b < a.n_buckets && !hot[t]) {
+            atomicMin(&base[sl[t]], cum[t]);
+            atomicMin(&lo[sl[t]], b);
+            atomicMax(&hi[sl[t]], b);
+        }
+        if (b < a.n_buckets && hot[t]) any_hot = 1;
+    }
+    __syncthreads();
+    // buckets [slice_lo, slice_hi] of a slice (an empty slice has hi < lo), and whether any bucket stays out of the index
+    for (int j = threadIdx.x; j < kMaxSlices; j += kScanThreads) {
+        a.slice_hot[kMaxSlices + j] = lo[j];
+        a.slice_hot[2 * kMaxSlices + j] = hi[j];
+    }
+    if (threadIdx.x == 0) a.slice_hot[3 * kMaxSlices] = any_hot;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+        const int b = threadIdx.x * PER + t;
+        if (b < a.n_buckets) {
+            a.slice_of[b] = sl[t];
+            a.bucket_start[b] = hot[t] ? 0 : cum[t] - base[sl[t]];
+        }
     }
 }
 
@@ -199,14 +272,40 @@ __global__ __launch_bounds__(kThreads) void part_scatter_kernel(InvertArgs a, Ti
         pos_scatter_block<(D_SC != 0 ? D_SC : 64)>(sc, (int64_t)blockIdx.x, reinterpret_cast<uint64_t *>(cur));
         return;
     }
-    const int64_t chunk = (int64_t)blockIdx.x - (D_SC != 0 ? sc_blocks : 0);
-    const int64_t n_chunks = (int64_t)gridDim.x - (D_SC != 0 ? sc_blocks : 0);
-    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) cur[b] = a.part_hist[(int64_t)b * n_chunks + chunk];
+    // Buckets of this slice: the block's cursor starts at the block's scanned offset inside the bucket, moved to where
+    // the bucket starts in the slice's arrays.  Buckets of other slices get a negative cursor and are skipped.
+    const int64_t blk = (int64_t)blockIdx.x - (D_SC != 0 ? sc_blocks : 0);
+    const int64_t nb = a.n_part_blocks;
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads)
+        cur[b] = (a.slice_of[b] == a.slice) ? a.part_hist[(int64_t)b * nb + blk] - a.part_hist[(int64_t)b * nb] + a.bucket_start[b] : -1;
     __syncthreads();
-    for_live_pairs(a, chunk, [&](int32_t id, int32_t pos) {
-        const int32_t slot = atomicAdd(&cur[id >> kBucketShift], 1);
-        a.tmp[slot] = make_int2(id, pos);
-    });
+    for (int64_t chunk = blk; chunk < a.n_chunks; chunk += nb)
+        for_live_pairs(a, chunk, [&](int32_t id, int32_t pos) {
+            int32_t *c = &cur[id >> kBucketShift];
+            if (*c >= 0) a.tmp[atomicAdd(c, 1)] = make_int2(id, pos);  // cursors only grow: the sign never changes
+        });
+}
+
+// Pairs of the buckets that stay out of the index (more than an eighth of the budget in 2048 consecutive ids): each is
+// scored and added to dE on its own, one thread per pair, d atomics.  A correctness path for extreme skew, not a fast one.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void hot_bucket_kernel(InvertArgs a)
+{
+    __shared__ int8_t is_hot[kMaxBuckets];
+    if (a.slice_hot[3 * kMaxSlices] == 0) return;  // no such bucket (block-uniform)
+    for (int b = threadIdx.x; b < a.n_buckets; b += kThreads) is_hot[b] = a.slice_of[b] == kSliceHot;
+    __syncthreads();
+    const T *Hp = static_cast<const T *>(a.H), *Ep = static_cast<const T *>(a.E);
+    for (int64_t chunk = blockIdx.x; chunk < a.n_chunks; chunk += gridDim.x)
+        for_live_pairs(a, chunk, [&](int32_t id, int32_t pos) {
+            if (!is_hot[id >> kBucketShift]) return;
+            const T *h = Hp + (int64_t)pos * a.d, *e = Ep + (int64_t)id * a.d;
+            float o = 0.f;
+            for (int t = 0; t < a.d; ++t) o = fmaf(load1(h + t), load1(e + t), o);
+            const float G = (a.g ? a.g[pos] : 1.f) * fast_exp(o - a.lse_in[pos]);
+            float *row = a.dE + (int64_t)id * a.d;
+            for (int t = 0; t < a.d; ++t) unsafeAtomicAdd(row + t, G * load1(h + t));
+        });
 }
 
 __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
@@ -214,10 +313,14 @@ __global__ __launch_bounds__(kScanThreads) void bucket_sort_kernel(InvertArgs a)
     __shared__ int32_t hist[kBucketIds];
     __shared__ int32_t lds[kScanThreads / 64 + 1];
     const int b = blockIdx.x;
+    if (a.slice_of[b] != a.slice) return;  // block-uniform
     const int64_t n_blocks1 = a.n_part_blocks;
-    // the bucket's range in tmp: from the scanned (bucket, block 0) entry to the next bucket's
-    const int32_t rb = a.part_hist[(int64_t)b * n_blocks1];
-    const int32_t re = (b + 1 < a.n_buckets) ? a.part_hist[(int64_t)(b + 1) * n_blocks1] : a.part_total[0];
+    // the bucket's range in tmp: it starts where the slice plan put it and holds as many pairs as the scanned (bucket,
+    // block 0) entries of this bucket and the next are apart
+    const int32_t s0 = a.part_hist[(int64_t)b * n_blocks1];
+    const int32_t s1 = (b + 1 < a.n_buckets) ? a.part_hist[(int64_t)(b + 1) * n_blocks1] : a.part_total[0];
+    const int32_t rb = a.bucket_start[b];
+    const int32_t re = rb + (s1 - s0);
     const int64_t id0 = (int64_t)b << kBucketShift;
     for (int k = threadIdx.x; k < kBucketIds; k += kScanThreads) hist[k] = 0;
     __syncthreads();
@@ -334,22 +437,34 @@ __device__ __forceinline__ void walk_segment(const InvertArgs &a, const float (&
 // kHotPairs instead, filed in a work list, and hot_item_kernel spreads the chunks over the chip and adds their partial
 // rows with atomics (d atomics per kHotPairs pairs).
 constexpr int kHotPairs = 256;
+constexpr int kItemBlocks = 16384;  // grid of the item pass over a slice
 
 // One group of LPR lanes per item: e_v stays in registers, the positions that sampled it are walked four at a time.
 template <typename T, int LPR>
 __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
 {
     constexpr int GPW = 64 / LPR;  // items per wavefront
+    constexpr int IPB = (kThreads / 64) * GPW;  // items per block and trip
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
-    const int64_t v = ((int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6)) * GPW + lane / LPR;
     const bool col_ok = c * 8 < a.d;
+    // items of this launch: the whole table, or the buckets of the slice at hand (a fixed grid strides over them)
+    int64_t v_lo = 0, v_hi = a.V;
+    if (a.slice_of) {
+        v_lo = (int64_t)a.slice_hot[kMaxSlices + a.slice] << kBucketShift;
+        v_hi = min(a.V, ((int64_t)a.slice_hot[2 * kMaxSlices + a.slice] + 1) << kBucketShift);
+    }
+    for (int64_t v0 = v_lo + (int64_t)blockIdx.x * IPB; v0 < v_hi; v0 += (int64_t)gridDim.x * IPB) {
+    const int64_t v = v0 + (threadIdx.x >> 6) * GPW + lane / LPR;
     int32_t r = 0, r_end = 0;
-    if (v < a.V) {
-        r = (v == 0) ? 0 : a.cursor[v - 1];
+    if (v < v_hi && (a.slice_of == nullptr || a.slice_of[v >> kBucketShift] == a.slice)) {
+        // cursor[v] is the end of item v's segment; it starts where the one before it ends, the first item of a bucket
+        // where the bucket starts in the slice's arrays (without slices: one running array over all items)
+        if (a.slice_of) r = ((v & (kBucketIds - 1)) == 0) ? a.bucket_start[v >> kBucketShift] : a.cursor[v - 1];
+        else r = (v == 0) ? 0 : a.cursor[v - 1];
         r_end = a.cursor[v];
     }
-    if (!__any(r < r_end)) return;
+    if (!__any(r < r_end)) continue;
     if (r_end - r > kHotPairs) {  // hot item: file its chunks and leave it to hot_item_kernel
         const int32_t n_chunks = (r_end - r + kHotPairs - 1) / kHotPairs;
         int32_t slot = 0;
@@ -381,6 +496,7 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
         row[0] = dx;
         row[1] = dy;
     }
+    }  // item groups of this block
 }
 
 // The chunks item_dE_kernel filed: one lane group per chunk, a fixed grid strides over the list.
@@ -422,12 +538,17 @@ hipError_t launch_item_dE(const InvertArgs &a, hipStream_t stream)
 {
     constexpr int items_per_block = (kThreads / 64) * (64 / LPR);
     ProfScope prof(PROF_ITEM_DE, stream);
-    if (!invert_partitioned(a.V)) {  // the partitioned index build has cleared the work-list counter on its way
+    if (!a.slice_of) {  // the sliced index build has cleared the work-list counters on its way (plan_slices_kernel)
         const hipError_t e = launch_fill_zero(a.hot_count, 1, stream);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((item_dE_kernel<T, LPR>), dim3((unsigned)((a.V + items_per_block - 1) / items_per_block)),
-                       dim3(kThreads), 0, stream, a);
+    // unsliced: one trip per block; sliced: the slice's item range is only known on the device, a grid of at most
+    // kItemBlocks strides over it
+    int64_t item_blocks = (a.V + items_per_block - 1) / items_per_block;
+    if (a.slice_of && item_blocks > kItemBlocks) item_blocks = kItemBlocks;
+    hipLaunchKernelGGL((item_dE_kernel<T, LPR>), dim3((unsigned)item_blocks), dim3(kThreads), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((hot_item_kernel<T, LPR>), dim3(kHotBlocks), dim3(kThreads), 0, stream, a);
     return hipGetLastError();
 }
@@ -471,11 +592,31 @@ hipError_t launch_sample(const Sampler &smp, int64_t n_pos, int32_t K, int32_t *
     return hipGetLastError();
 }
 
-size_t invert_hot_capacity(int64_t N, int64_t K) { return (size_t)(2 * (N * K / kHotPairs) + 16); }
+int64_t invert_pair_budget(int64_t N, int64_t K)
+{
+    const int64_t pairs = N * K, eighth = (pairs + 7) / 8;
+    return eighth > kMinPairBudget ? eighth : kMinPairBudget;
+}
+int invert_slices(int64_t N, int64_t K)
+{
+    const int64_t pairs = N * K, B = invert_pair_budget(N, K), room = B - B / 8;
+    return pairs <= B ? 1 : (int)((pairs + room - 1) / room);
+}
+int64_t invert_index_pairs(int64_t N, int64_t K)   // entries of the arrays the index is filed into
+{
+    const int64_t pairs = N * K, B = invert_pair_budget(N, K);
+    return pairs < B ? pairs : B;
+}
+size_t invert_hot_capacity(int64_t N, int64_t K) { return (size_t)(2 * (invert_index_pairs(N, K) / kHotPairs) + 16); }
 size_t invert_scan_blocks(int64_t n) { return (size_t)((n + kScanChunk - 1) / kScanChunk); }
-int64_t invert_part_blocks(int64_t N, int64_t K) { return (N * K + kChunkPairs - 1) / kChunkPairs; }
+int64_t invert_part_blocks(int64_t N, int64_t K)
+{
+    const int64_t chunks = (N * K + kChunkPairs - 1) / kChunkPairs;
+    return chunks < kMaxPartBlocks ? chunks : kMaxPartBlocks;
+}
 int64_t invert_buckets(int64_t V) { return (V + kBucketIds - 1) / kBucketIds; }
 bool invert_partitioned(int64_t V) { return invert_buckets(V) <= kMaxBuckets; }
+int invert_plan_words() { return 3 * kMaxSlices + 8; }  // work-list counters, first and last bucket of every slice, one flag
 
 hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, const TileArgs *scatter, hipStream_t stream)
 {
@@ -484,16 +625,47 @@ hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, const TileArgs 
     if (a.K == 0) return scatter ? launch_pos_scatter(*scatter, stream) : hipSuccess;
     const int64_t pairs = a.N * a.K;
     hipError_t e;
+    auto check = [&]() { return (e = hipGetLastError()) == hipSuccess; };
+    if (!invert_partitioned(a.V)) {
+        // catalogue too large for the LDS bucket histogram (the caller only comes here when all pairs fit the budget):
+        // counting sort with integer atomics on the V-word table, one running array over all items
+        a.slice_of = nullptr;
+        a.bucket_start = nullptr;
+        {
+            ProfScope prof(PROF_INDEX, stream);
+            if (scatter && (e = launch_pos_scatter(*scatter, stream)) != hipSuccess) return e;
+            const unsigned pair_blocks = (unsigned)((pairs + kThreads - 1) / kThreads);
+            if ((e = launch_fill_zero(a.cursor, (size_t)a.V, stream)) != hipSuccess) return e;
+            hipLaunchKernelGGL(count_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
+            if (!check()) return e;
+            if ((e = launch_scan(a.cursor, a.V, a.block_sums, stream)) != hipSuccess) return e;
+            hipLaunchKernelGGL(fill_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
+            if (!check()) return e;
+        }
+        return bf16 ? launch_item_dE_by_width<uint16_t>(a, stream) : launch_item_dE_by_width<float>(a, stream);
+    }
+    a.n_buckets = (int32_t)invert_buckets(a.V);
+    a.n_part_blocks = invert_part_blocks(a.N, a.K);
+    a.n_chunks = (pairs + kChunkPairs - 1) / kChunkPairs;
+    a.budget = invert_pair_budget(a.N, a.K);
+    a.n_slices = invert_slices(a.N, a.K);
+    if (a.n_slices > kMaxSlices) return hipErrorInvalidValue;  // cannot happen: at most 11 by construction
+    const int64_t n_hist = (int64_t)a.n_buckets * a.n_part_blocks;
+    a.part_total = a.part_hist + n_hist;  // one extra word: scanning n_hist + 1 entries leaves the grand total there
     {
         ProfScope prof(PROF_INDEX, stream);
-        if (invert_partitioned(a.V)) {
-            a.n_buckets = (int32_t)invert_buckets(a.V);
-            a.n_part_blocks = invert_part_blocks(a.N, a.K);
-            const int64_t n_hist = (int64_t)a.n_buckets * a.n_part_blocks;
-            a.part_total = a.part_hist + n_hist;  // one extra word: scanning n_hist + 1 entries leaves the grand total there
-            hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
-            if ((e = launch_scan(a.part_hist, n_hist + 1, a.block_sums, stream)) != hipSuccess) return e;
-            if (scatter) {  // the correct items' rows ride at the head of this launch
+        hipLaunchKernelGGL(part_count_kernel, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+        if (!check()) return e;
+        if ((e = launch_scan(a.part_hist, n_hist + 1, a.block_sums, stream)) != hipSuccess) return e;
+        hipLaunchKernelGGL(plan_slices_kernel, dim3(1), dim3(kScanThreads), 0, stream, a);
+        if (!check()) return e;
+    }
+    for (int32_t j = 0; j < a.n_slices; ++j) {
+        a.slice = j;
+        a.hot_count = a.slice_hot + j;
+        {
+            ProfScope prof(PROF_INDEX, stream);
+            if (scatter && j == 0) {  // the correct items' rows ride at the head of the first filing launch
                 const int64_t sc_blocks = (scatter->N + kPosChunk - 1) / kPosChunk;
                 const dim3 grid((unsigned)(a.n_part_blocks + sc_blocks));
                 switch (scatter->d) {
@@ -505,18 +677,20 @@ hipError_t launch_inverted_dE(bool bf16, const InvertArgs &a_in, const TileArgs 
             } else {
                 hipLaunchKernelGGL(part_scatter_kernel<0>, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a, TileArgs{}, 0);
             }
+            if (!check()) return e;
             hipLaunchKernelGGL(bucket_sort_kernel, dim3((unsigned)a.n_buckets), dim3(kScanThreads), 0, stream, a);
-        } else {
-            if (scatter && (e = launch_pos_scatter(*scatter, stream)) != hipSuccess) return e;
-            const unsigned pair_blocks = (unsigned)((pairs + kThreads - 1) / kThreads);
-            if ((e = launch_fill_zero(a.cursor, (size_t)a.V, stream)) != hipSuccess) return e;
-            hipLaunchKernelGGL(count_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
-            if ((e = launch_scan(a.cursor, a.V, a.block_sums, stream)) != hipSuccess) return e;
-            hipLaunchKernelGGL(fill_kernel, dim3(pair_blocks), dim3(kThreads), 0, stream, a);
+            if (!check()) return e;
         }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        e = bf16 ? launch_item_dE_by_width<uint16_t>(a, stream) : launch_item_dE_by_width<float>(a, stream);
+        if (e != hipSuccess) return e;
     }
-    return bf16 ? launch_item_dE_by_width<uint16_t>(a, stream) : launch_item_dE_by_width<float>(a, stream);
+    if (a.n_slices > 1) {  // buckets too crowded for any slice, if there are any
+        ProfScope prof(PROF_ITEM_DE, stream);
+        if (bf16) hipLaunchKernelGGL(hot_bucket_kernel<uint16_t>, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+        else hipLaunchKernelGGL(hot_bucket_kernel<float>, dim3((unsigned)a.n_part_blocks), dim3(kThreads), 0, stream, a);
+        if (!check()) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace cce

@@ -86,8 +86,13 @@ struct InvertArgs {
     float *dE;
     int32_t *cursor;         // [V] workspace: counts -> segment starts -> segment ends
     int32_t *block_sums;     // [invert_scan_blocks(V)] workspace
-    int32_t *pairs;          // [N*K] workspace: positions filed under their item
-    int2 *tmp;               // [N*K] workspace: (id, position) partitioned by bucket
+    int32_t *pairs;          // [invert_index_pairs] workspace: positions filed under their item (of the slice at hand)
+    int2 *tmp;               // [invert_index_pairs] workspace: (id, position) partitioned by bucket (of the slice at hand)
+    int32_t *bucket_start;   // [n_buckets] workspace: where a bucket starts in the arrays of its slice (nullptr: unsliced)
+    int32_t *slice_of;       // [n_buckets] workspace: slice of every bucket, -1 = out of the index (nullptr: unsliced)
+    int32_t *slice_hot;      // [invert_plan_words] workspace: per slice the work-list counter, first and last bucket; a flag
+    int64_t budget, n_chunks;  // pairs per slice at most; chunks of 8192 pairs in all
+    int32_t n_slices, slice;   // slices of this call; the one this launch works on
     int32_t *part_hist;      // [n_buckets * n_part_blocks + 1] workspace: (bucket, block) counts -> offsets
     int32_t *part_total;     // = part_hist + n_buckets * n_part_blocks (set by the launcher)
     int4 *hot_list;          // [hot_capacity] workspace: (item, first pair, end pair, -) chunks of items with long segments
@@ -98,6 +103,10 @@ struct InvertArgs {
     Sampler smp;             // kind != 0: the negatives are drawn again here instead of being read from neg
 };
 size_t invert_hot_capacity(int64_t N, int64_t K);  // entries of hot_list
+int64_t invert_pair_budget(int64_t N, int64_t K);  // pairs one slice of the index holds at most
+int64_t invert_index_pairs(int64_t N, int64_t K);  // entries of pairs / tmp: min(N K, budget)
+int invert_slices(int64_t N, int64_t K);           // slices of the item-id range the index is built in
+int invert_plan_words();                           // words of slice_hot
 size_t invert_scan_blocks(int64_t n);          // blocks of the scan over n words (size of block_sums)
 int64_t invert_part_blocks(int64_t N, int64_t K);
 int64_t invert_buckets(int64_t V);

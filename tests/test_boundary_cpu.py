@@ -49,6 +49,17 @@ def test_workspace_bytes_rejects_bad_descriptors(binding):
     b = B.cce_neg_workspace_bytes(B.make_desc(51200, 50000, 64, 10240, B.CCE_BF16, B.CCE_NEG_SHARED))
     c = B.cce_neg_workspace_bytes(B.make_desc(512000, 50000, 64, 10240, B.CCE_BF16, B.CCE_NEG_SHARED))
     assert b <= a + 10240 * 64 * 16 and c <= b + 512000 * 64 * 8
+    # per-position mode: the inverted index is built in slices of a fixed pair budget, so ten times the negatives must
+    # not cost ten times the workspace, and the index never outgrows 3/8 of the id matrix (4 N K bytes) plus O(N + V)
+    def pp(N, V, K, d=128):
+        return B.cce_neg_workspace_bytes(B.make_desc(N, V, d, K, B.CCE_BF16, B.CCE_NEG_PER_POSITION))
+    c3 = pp(25600, 1_000_000, 256)
+    assert c3 <= 12.2 * (1 << 22) + 4 * 1_000_000 + 4 * 25600 + (4 << 20)       # one slice of 2^22 pairs, not 12 N K = 79 MB
+    assert pp(25600, 1_000_000, 2560) <= 2.1 * c3
+    big = pp(204800, 1_000_000, 2560)                                           # 524 M pairs
+    assert big <= 0.375 * 4 * 204800 * 2560 * 1.05 + 4 * 1_000_000 + 4 * 204800 + (34 << 20)
+    assert pp(1024, 5_000_000, 16) > 4 * 5_000_000                             # huge catalogue, few pairs: indexed (cursor per item)
+    assert pp(204800, 5_000_000, 256) == 256                                    # huge catalogue, many pairs: atomics, header only
 
 
 def test_forward_backward_reject_null_and_small_workspace_before_launch(binding):

@@ -676,3 +676,38 @@ def test_random_medium_shapes_on_the_matrix_core_path(seed):
     reuse = bool(rng.integers(0, 2))
     print(dict(mode=mode, d=d, N=w.N, V=V, K=K, pad=pad, collide=w.mask_collisions, reuse=reuse))
     check_against_oracle(w, _run(w, algo=P.CCE_ALGO_TILE, reuse_prep=reuse), TOL_BF16)
+
+
+@pytest.mark.parametrize("case", ["ordinary_buckets", "one_crowded_bucket", "power_law"])
+def test_per_position_index_built_in_slices(case):
+    """More (position, negative) pairs than one slice of the inverted index holds (2^22): the index is built and used
+    up slice by slice over the item-id range.  ordinary_buckets: uniform ids over 147 buckets, two slices.
+    one_crowded_bucket: a catalogue of 1000 items, so all 8.4 M pairs fall into one bucket of 2048 ids, more than a
+    eighth of the budget: the bucket stays out of the index and its pairs are added with atomics.  power_law: the
+    head item's bucket is crowded, the others are sliced."""
+    import dataclasses
+
+    from workloads import zipf_ids
+
+    if case == "ordinary_buckets":
+        w = make_workload("slices", 100, 200, 64, 300_000, 300, "bf16", NEG_PER_POSITION, 77, g_kind="random", pad="bernoulli",
+                          pad_p=0.1, tgt_dist="zipf")
+    elif case == "one_crowded_bucket":
+        w = make_workload("slices_hot", 128, 128, 64, 1000, 512, "bf16", NEG_PER_POSITION, 78, g_kind="random", pad="none")
+    else:
+        w = make_workload("slices_zipf", 100, 200, 64, 50_000, 300, "bf16", NEG_PER_POSITION, 79, g_kind="random", pad="right",
+                          pad_len_lo=150)
+        rng = np.random.default_rng(6)
+        ids, _ = zipf_ids(rng, rng, w.N * w.K, w.V, 1.3)
+        w = dataclasses.replace(w, neg=ids.reshape(w.N, w.K))
+    assert w.N * w.K > (1 << 22)
+    counts = np.bincount((w.neg[w.mask != 0].ravel() >> 11), minlength=(w.V + 2047) >> 11)
+    print(case, "pairs", w.N * w.K, "buckets", counts.size, "largest bucket", int(counts.max()))
+    if case != "ordinary_buckets":
+        assert counts.max() > (1 << 19)      # beyond an eighth of the budget
+    if case == "power_law":
+        # the head item's dE row is a sum of over a million terms of both signs, taken by fp32 atomics in arrival order:
+        # its rounding error is that of the summation (about sqrt(n) * 2^-24 of the sum of magnitudes), not of the terms
+        check_against_oracle(w, _run(w), 2e-3, row_tol=2e-3)
+    else:
+        check_against_oracle(w, _run(w), 2e-5)
