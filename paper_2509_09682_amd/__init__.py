@@ -6,4 +6,4 @@ from .binding import (  # noqa: F401
     CCE_SAMPLER_ALIAS, CCE_SAMPLER_UNIFORM, CceSampler, cce_neg_backward_sampled, cce_neg_forward_sampled, cce_neg_sample,
     make_sampler, cce_neg_workspace_bytes, cce_neg_workspace_init, cce_neg_profile_enable, cce_neg_profile_read, make_desc, new_workspace, status_string,
 )
-from .autograd import cce_neg_loss  # noqa: F401,E402
+from .autograd import cce_neg_loss, clear_workspaces  # noqa: F401,E402
