@@ -7,3 +7,4 @@ from .binding import (  # noqa: F401
     make_sampler, cce_neg_workspace_bytes, cce_neg_workspace_init, cce_neg_profile_enable, cce_neg_profile_read, make_desc, new_workspace, status_string,
 )
 from .autograd import cce_neg_loss, clear_workspaces  # noqa: F401,E402
+from .consumers import bucketed_step  # noqa: F401,E402
