@@ -461,8 +461,12 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
                 a_de.scale_blocks = 1;
                 return cce::launch_tile(cce::TILE_PASS_DE, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
             }
-            if (cce::launch_dh_scale(a, true, stream) != hipSuccess) return CCE_ERR_HIP;
-            a_de.g_stream_off = 1;  // the dE pass reads grad_loss where the scaling pass has just filed it
+            a_de.g_stream_off = 1;  // the dE pass reads grad_loss where the scaling pass has filed it
+            if (cce::tile_backward_fusable(desc->d)) {  // no grad_loss array to stream: scale (and file ones) first
+                if (cce::launch_dh_scale(a, true, stream) != hipSuccess) return CCE_ERR_HIP;
+            } else {
+                a_de.scale_blocks = 1;  // hidden size 256: the scaling shares the launch of the correct-item scatter
+            }
             return cce::launch_tile(cce::TILE_PASS_DE, a_de, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
         }
         if (cce::tile_backward_fusable(desc->d))  // both passes in one launch, behind a small per-position pass

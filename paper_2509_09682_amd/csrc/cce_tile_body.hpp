@@ -32,6 +32,10 @@
 #include "cce_tile_shared.hpp"
 
 namespace cce {
+
+template <int D>
+hipError_t launch_pos_scatter_scale_d(const TileArgs &a, hipStream_t stream);  // defined at the end of this header
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -1787,7 +1791,10 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
             // at a time, one long latency chain each, before any tile block starts (c5: 330 us of a 970 us launch).
             // On their own they run many to a compute unit.
             a.scatter_apart = 1;
-            if ((e = launch_pos_scatter(a, stream)) != hipSuccess) return e;
+            if (a.scale_blocks > 0) {  // dH = grad_loss * U wanted as well: next to the scatter, not behind the tiles
+                a.scale_blocks = 0;
+                if ((e = launch_pos_scatter_scale_d<D>(a, stream)) != hipSuccess) return e;
+            } else if ((e = launch_pos_scatter(a, stream)) != hipSuccess) return e;
         }
         if constexpr (XG_B == 2) {
             if (wide(a.n_cols, false)) return launch_tile_kernel<D, MODE_DE, BY_B, 4, 2, MINB, NBUF_B>(a, a.n_cols, stream);
@@ -1847,6 +1854,36 @@ __global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
 {
     __shared__ uint64_t keys[kPosChunk];
     pos_scatter_block<D>(a, blockIdx.x, keys);
+}
+
+// The correct-item scatter and the scaling dH = grad_loss * U in one launch (hidden size 256, where neither rides in
+// the dE launch): the scatter is bound by latencies and atomics, the scaling by memory bandwidth, and they share no
+// data, so side by side they take about as long as the scatter alone.  The scaling blocks also file grad_loss under the
+// compacted index for the dE pass that follows.
+template <int D>
+__global__ __launch_bounds__(kPosChunk) void pos_scatter_scale_kernel(TileArgs a, int64_t scatter_blocks)
+{
+    __shared__ uint64_t keys[kPosChunk];
+    static_assert(kPosChunk == 256, "the scaling role indexes 256 threads per block");
+    if ((int64_t)blockIdx.x < scatter_blocks) {
+        pos_scatter_block<D>(a, blockIdx.x, keys);
+        return;
+    }
+    const int64_t chunk = ((int64_t)blockIdx.x - scatter_blocks) * 256 + threadIdx.x;
+    const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
+    if (chunk < n_pos) a.de_const[a.N + chunk] = __float_as_uint(a.g ? a.g[pos_row(a, chunk)] : 1.f);
+    dh_scale_chunk<D>(a, chunk);
+}
+
+template <int D>
+hipError_t launch_pos_scatter_scale_d(const TileArgs &a, hipStream_t stream)
+{
+    if (a.N == 0) return hipSuccess;
+    const int64_t scatter_blocks = (a.N + kPosChunk - 1) / kPosChunk, scale_blocks = (a.N * (D / 8) + 255) / 256;
+    ProfScope prof(PROF_POS_SCATTER, stream);
+    hipLaunchKernelGGL((pos_scatter_scale_kernel<D>), dim3((unsigned)(scatter_blocks + scale_blocks)), dim3(kPosChunk), 0, stream, a,
+                       scatter_blocks);
+    return hipGetLastError();
 }
 
 template <int D>
