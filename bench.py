@@ -106,7 +106,8 @@ def kernel_work(w, family):
 
 
 def measured_traffic(workload, family):
-    """HBM bytes per launch measured with rocprofv3 counters and kept under profiles/ (None when no record exists)."""
+    """HBM bytes per step of a kernel family, measured with rocprofv3 counters and kept under profiles/ (None when no
+    record exists for this workload and family)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
         return None
@@ -234,8 +235,10 @@ def measure(w, args, *, headline: bool) -> dict:
     fam = P.cce_neg_profile_read()
     P.cce_neg_profile_enable(False)
     kernels = {k: {"avg_ms": ms / n, "launches_per_step": n / steps} for k, (ms, n) in fam.items()}
+    # the dominant kernel family and its time per step (a family that launches several times per step, e.g. the item pass
+    # of the sliced inverted index, is taken as a whole: its algorithmic work below is per step as well)
     dominant = max(fam, key=lambda k: fam[k][0])
-    dom_ms = fam[dominant][0] / fam[dominant][1]
+    dom_ms = fam[dominant][0] / steps
 
     flops, bytes_min = algorithmic_work(w)
     bound, work = kernel_work(w, dominant)
@@ -249,6 +252,7 @@ def measure(w, args, *, headline: bool) -> dict:
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(w.name, dominant)
     roof["avg_launch_ms"] = dom_ms
+    roof["launches_per_step"] = fam[dominant][1] / steps
     roof["algorithmic_per_launch"] = work
 
     mfma_bound = w.in_dtype == "bf16" and w.neg_mode != 1
