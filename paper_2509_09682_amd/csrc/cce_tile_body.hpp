@@ -449,21 +449,29 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
             rows[i] = ind ? checked_row(ind[y]) : (int32_t)y;
         }
     };
+    // Everything per lane in here is recomputed from the thread number at every step: kept across the loop, these
+    // values are the first that the register allocator spills, and a reload from scratch memory waits, as the counter of
+    // vector-memory operations runs in order, for every tile load in flight.
     auto rows_from_lds = [&](int64_t t, const uint16_t *holder, int32_t (&rows)[NR]) {
         const int32_t *ids = reinterpret_cast<const int32_t *>(holder + OFF_I);
+        const uint32_t y0 = (uint32_t)(t * BY), y_last = (uint32_t)(n_y - 1);  // t * BY < n_y < 2^31
+        uint32_t me = (uint32_t)tid;
+        asm volatile("" : "+v"(me));
+        const uint32_t r0 = me / CPR;  // CPR divides 64: instruction i of this lane fetches row r0 + i * (NW * 64 / CPR)
         rows[LPW] = 0;
         if (GSEP && a.g_separate && !a.g_stream_off) {
-            const int64_t y = t * BY + const_row_slot();
-            rows[LPW] = ind ? ids[const_row_slot()] : (int32_t)(y < n_y ? y : n_y - 1);
+            const uint32_t slot = (((me >> 6) % CI) * 64 + (me & 63)) % BY;  // const_row_slot()
+            const uint32_t y = y0 + slot;
+            rows[LPW] = ind ? ids[slot] : (int32_t)(y < y_last ? y : y_last);
         }
         if (ind) {
 #pragma unroll
-            for (int i = 0; i < LPW; ++i) rows[i] = checked_row(ids[((wave + i * NW) * 64 + lane) / CPR]);
+            for (int i = 0; i < LPW; ++i) rows[i] = checked_row(ids[r0 + i * (NW * 64 / CPR)]);
         } else {
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                const int64_t y = t * BY + ((wave + i * NW) * 64 + lane) / CPR;
-                rows[i] = (int32_t)(y < n_y ? y : n_y - 1);
+                const uint32_t y = y0 + r0 + (uint32_t)(i * (NW * 64 / CPR));
+                rows[i] = (int32_t)(y < y_last ? y : y_last);
             }
         }
     };
@@ -500,7 +508,9 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
         } else {
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                const char *src = Ybytes + (int64_t)rows[i] * (D * 2) + chunk_ofs[i];
+                uint32_t co = chunk_ofs[i];
+                asm volatile("" : "+v"(co));  // keeps the per-lane sum Ybytes + chunk_ofs from being carried (and spilled) as a 64-bit pair
+                const char *src = Ybytes + ((int64_t)rows[i] * (D * 2) + co);
                 __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + (wave + i * NW) * 512), 16, 0, 0);
             }
         }
@@ -1697,13 +1707,14 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
     // the 256-register budget: operands are read two at a time there.
     constexpr int NW_L = (D <= 128) ? 4 : 8;
     constexpr int DS_B = 1;
-    constexpr int BY_B = BY;
+    constexpr int BY_B = BY;  // d = 256: tiles of 64 rows measured 3-6 % slower
     constexpr int MINB = (D <= 128) ? 2 : 1;   // backward: 256 registers per wavefront
     // LDS buffers in flight, 18 KiB each: three blocks per compute unit leave room for three of them, two blocks or
     // one for four.  d = 256: two 66-KiB buffers in the forward pass; three buffers in the backward passes (measured:
     // dE 5 % faster than with two, dH unchanged, four no better).
     constexpr int NBUF_F = (D <= 64) ? 3 : (D <= 128 ? 4 : 2);
     constexpr int NBUF_B = (D <= 128) ? 4 : 3;
+    constexpr int NBUF_FDH = 4;  // d = 256: 2 % faster than three (the dE pass: 20 % slower)
     // Two groups of stationary rows per wavefront use each LDS operand for two matrix instructions; the backward
     // accumulators leave room for that up to d = 64.
     constexpr int XG_F = 2;
@@ -1767,7 +1778,7 @@ hipError_t launch_for_d(int pass, TileArgs a, hipStream_t stream)
                 done = true;
             }
         }
-        if (!done) e = launch_tile_kernel<D, MODE_FDH, BY_B, NW_L, 1, MINB, NBUF_B, DS_B>(a, a.N, stream);
+        if (!done) e = launch_tile_kernel<D, MODE_FDH, BY_B, NW_L, 1, MINB, NBUF_FDH, DS_B>(a, a.N, stream);
         if constexpr (D > 128) {
             if (e == hipSuccess && a.tail_slots > 0) {
                 constexpr int PPB = 256 / (D / 8), XPB_L = NW_L * 32;
