@@ -65,6 +65,7 @@ Layout make_layout(const cce_desc *d)
     int sd = (cblocks > 0) ? (int)(2048 / cblocks) : 1;
     const int64_t pos_tiles = (N + by - 1) / by;
     if (sd > 128) sd = 128;
+    if (sd < 8) sd = 8;  // merged by atomics, no buffer depends on it: room to even out a grid of one or two rounds
     if (sd > pos_tiles / 2) sd = (int)(pos_tiles / 2);
     if (sd < 1) sd = 1;
     L.splits_de = sd;

@@ -1604,11 +1604,17 @@ int resident_blocks(K kernel, int threads)
 
 // Split factor in [1, max_splits] that wastes the least of the last round of blocks; ties go to the smaller factor,
 // and a factor is only raised for a gain of at least five percent.
-inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_merge)
+inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_merge, bool atomic_merge)
 {
     // enough blocks already: a split costs partial results and a merge.  Where the merge is cheap (forward: two floats
-    // per position and split) a grid of a few rounds is still split to even out its last round.
-    if (xblocks * 4 > slots && !(cheap_merge && xblocks > slots && xblocks < 8 * (int64_t)slots)) return 1;
+    // per position and split) a grid of a few rounds is still split to even out its last round.  The dE pass merges by
+    // atomics under the other blocks' matrix work: a grid of less than two rounds is split when that fills the last
+    // round at least 15 % better (c4: 391 blocks on 512 slots, 405 us unsplit, 367 us in 5 splits).
+    double min_gain = 1.05;
+    if (xblocks * 4 > slots && !(cheap_merge && xblocks > slots && xblocks < 8 * (int64_t)slots)) {
+        if (!(atomic_merge && xblocks < 2 * (int64_t)slots)) return 1;
+        min_gain = 1.15;
+    }
     int best = 1;
     double best_eff = 0.0;
     for (int s = 1; s <= max_splits; ++s) {
@@ -1618,7 +1624,7 @@ inline int pick_splits(int64_t xblocks, int max_splits, int slots, bool cheap_me
         // forward pass: the block count is an upper bound when positions are padded, and every split repeats the
         // block prologue: the first factor that fills the last round reasonably is taken (c5: 2 instead of 4, 394 -> 361 us)
         if (cheap_merge && eff >= 0.88) return s;
-        if (eff > best_eff * 1.05) {
+        if (eff > best_eff * (s == 1 ? 0.0 : min_gain)) {
             best_eff = eff;
             best = s;
         }
@@ -1641,7 +1647,7 @@ int64_t plan_tile_grid(TileArgs &a, int64_t n_x, int xpb, int threads, int slots
         if (a.splits > cap) a.splits = cap;
     }
     const int max_splits = a.splits;
-    a.splits = pick_splits(xblocks, a.splits, slots, MODE == MODE_FWD);
+    a.splits = pick_splits(xblocks, a.splits, slots, MODE == MODE_FWD, MODE == MODE_DE);
     if (fine && a.splits > 1) a.splits = max_splits;
     int64_t blocks = xblocks * a.splits;
     if (MODE == MODE_DE) {  // the latency-bound scatter blocks go first so that they run under the matrix work
