@@ -13,19 +13,21 @@ __device__ __forceinline__ int64_t pos_row(const TileArgs &a, int64_t x) { retur
 // LDS; every wavefront then walks 64 consecutive sorted pairs with lane = column, sums runs of equal targets in
 // registers and issues one row of atomics per run.  These blocks ride at the head of another launch (the dE pass of the
 // matrix-core path, the second index pass of the per-position path), so that their latency (sort, dependent gathers)
-// hides under that launch's own work.
-constexpr int kPosChunk = 256;
+// hides under that launch's own work.  Where the scatter is a launch of its own a block sorts 1024 pairs: longer runs
+// of equal targets, fewer rows of atomics (largest workload: 60 k instead of 78 k).
+constexpr int kPosChunk = 256;        // pairs per block riding in another launch
+constexpr int kPosChunkApart = 1024;  // pairs per block of the stand-alone scatter kernels
 
-template <int D>
+template <int D, int CHUNK = kPosChunk>
 __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chunk, uint64_t *keys)
 {
     constexpr int CPL = D / 64;         // columns per lane
     constexpr int kPosBatch = 16;        // rows in flight per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
-    const int64_t base = chunk * kPosChunk;
+    const int64_t base = chunk * CHUNK;
     if (base >= n_pos) return;
-    const bool sorter = tid < kPosChunk;  // blocks of more than 256 threads: the rest only keep the barriers company
+    const bool sorter = tid < CHUNK;  // blocks of more threads than pairs: the rest only keep the barriers company
     if (sorter) {
         uint64_t key = ~0ull;  // padding sorts last
         if (base + tid < n_pos) {
@@ -38,7 +40,7 @@ __device__ __forceinline__ void pos_scatter_block(const TileArgs &a, int64_t chu
         keys[tid] = key;
     }
     __syncthreads();
-    for (int k = 2; k <= kPosChunk; k <<= 1) {
+    for (int k = 2; k <= CHUNK; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             const int partner = tid ^ j;
             if (sorter && partner > tid) {

@@ -1867,10 +1867,10 @@ hipError_t launch_bwd_for_d(TileArgs a_dh, TileArgs a_de, hipStream_t stream)
 }  // namespace
 
 template <int D>
-__global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
+__global__ __launch_bounds__(kPosChunkApart) void pos_scatter_kernel(TileArgs a)
 {
-    __shared__ uint64_t keys[kPosChunk];
-    pos_scatter_block<D>(a, blockIdx.x, keys);
+    __shared__ uint64_t keys[kPosChunkApart];
+    pos_scatter_block<D, kPosChunkApart>(a, blockIdx.x, keys);
 }
 
 // The correct-item scatter and the scaling dH = grad_loss * U in one launch (hidden size 256, where neither rides in
@@ -1878,15 +1878,14 @@ __global__ __launch_bounds__(kPosChunk) void pos_scatter_kernel(TileArgs a)
 // data, so side by side they take about as long as the scatter alone.  The scaling blocks also file grad_loss under the
 // compacted index for the dE pass that follows.
 template <int D>
-__global__ __launch_bounds__(kPosChunk) void pos_scatter_scale_kernel(TileArgs a, int64_t scatter_blocks)
+__global__ __launch_bounds__(kPosChunkApart) void pos_scatter_scale_kernel(TileArgs a, int64_t scatter_blocks)
 {
-    __shared__ uint64_t keys[kPosChunk];
-    static_assert(kPosChunk == 256, "the scaling role indexes 256 threads per block");
+    __shared__ uint64_t keys[kPosChunkApart];
     if ((int64_t)blockIdx.x < scatter_blocks) {
-        pos_scatter_block<D>(a, blockIdx.x, keys);
+        pos_scatter_block<D, kPosChunkApart>(a, blockIdx.x, keys);
         return;
     }
-    const int64_t chunk = ((int64_t)blockIdx.x - scatter_blocks) * 256 + threadIdx.x;
+    const int64_t chunk = ((int64_t)blockIdx.x - scatter_blocks) * kPosChunkApart + threadIdx.x;
     const int64_t n_pos = a.n_valid_ptr ? (int64_t)*a.n_valid_ptr : a.N;
     if (chunk < n_pos) a.de_const[a.N + chunk] = __float_as_uint(a.g ? a.g[pos_row(a, chunk)] : 1.f);
     dh_scale_chunk<D>(a, chunk);
@@ -1896,9 +1895,10 @@ template <int D>
 hipError_t launch_pos_scatter_scale_d(const TileArgs &a, hipStream_t stream)
 {
     if (a.N == 0) return hipSuccess;
-    const int64_t scatter_blocks = (a.N + kPosChunk - 1) / kPosChunk, scale_blocks = (a.N * (D / 8) + 255) / 256;
+    const int64_t scatter_blocks = (a.N + kPosChunkApart - 1) / kPosChunkApart;
+    const int64_t scale_blocks = (a.N * (D / 8) + kPosChunkApart - 1) / kPosChunkApart;
     ProfScope prof(PROF_POS_SCATTER, stream);
-    hipLaunchKernelGGL((pos_scatter_scale_kernel<D>), dim3((unsigned)(scatter_blocks + scale_blocks)), dim3(kPosChunk), 0, stream, a,
+    hipLaunchKernelGGL((pos_scatter_scale_kernel<D>), dim3((unsigned)(scatter_blocks + scale_blocks)), dim3(kPosChunkApart), 0, stream, a,
                        scatter_blocks);
     return hipGetLastError();
 }
@@ -1918,7 +1918,7 @@ template <int D>
 hipError_t launch_pos_scatter_d(const TileArgs &a, hipStream_t stream)
 {
     if (a.N == 0) return hipSuccess;
-    const dim3 grid((unsigned)((a.N + kPosChunk - 1) / kPosChunk)), block(kPosChunk);
+    const dim3 grid((unsigned)((a.N + kPosChunkApart - 1) / kPosChunkApart)), block(kPosChunkApart);
     ProfScope prof(PROF_POS_SCATTER, stream);
     hipLaunchKernelGGL((pos_scatter_kernel<D>), grid, block, 0, stream, a);
     return hipGetLastError();
