@@ -482,8 +482,13 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
     p.dE = dE;
     p.smp = smp;
     if (!cce::use_inverted(desc)) {
-        const hipError_t e = cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream);
-        return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+        // Shared negatives or the full catalogue: the position-major pass yields dH and the correct items' dE rows; the
+        // rows of the shared candidates, which every position updates, come from a candidate-major pass.
+        const bool shared_rows = desc->neg_mode != CCE_NEG_PER_POSITION;
+        if (shared_rows) p.skip_neg_dE = 1;
+        if (cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream) != hipSuccess) return CCE_ERR_HIP;
+        if (shared_rows && cce::launch_shared_dE(desc->in_dtype == CCE_BF16, p, stream) != hipSuccess) return CCE_ERR_HIP;
+        return CCE_OK;
     }
     // Per-position negatives: the row-gather pass yields dH and the correct-item coefficients; dE of the negatives
     // comes from the inverted-index pass, dE of the correct items from the aggregated scatter where it exists.

@@ -11,6 +11,8 @@ enum { kHdrStatus = 0, kHdrTotal = 1, kHdrDone = 2, kHdrNValid = 3, kHdrHot = 4 
 
 // ---- row-gather family: one wavefront per position; any mode, fp32 or bf16 inputs
 hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream);
+// dE of the negatives shared by all positions (shared list or full catalogue), candidate-major; row-gather family
+hipError_t launch_shared_dE(bool bf16, const Params &p, hipStream_t stream);
 
 // ---- matrix-core family: bf16 inputs, shared negatives or full catalogue
 struct PrepArgs {
