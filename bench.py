@@ -53,13 +53,15 @@ def algorithmic_work(w):
     return flops, gathered + dE_bytes + ids + per_pos
 
 
-def kernel_work(w, family):
+def kernel_work(w, family, fused=False):
     """Algorithmic work of ONE launch of a kernel family: ("mfma", flops) or ("hbm", bytes).
 
     Matrix-core kernels: 2 * n_cols * d flop per valid position and GEMM-equivalent, n_cols = K (V for the full
-    catalogue).  The forward pass is one GEMM-equivalent (scores), the dH pass two (scores recomputed, dH), the dE pass
-    one (dE; its own recomputation of the scores is overhead and does not count); hidden sizes up to 128 run the dH and
-    the dE pass in one launch (tile_bwd, three).
+    catalogue).  A step has four of them (scores, scores recomputed in the backward pass as in Alg. 2, dH, dE), and each
+    is counted in the launch that carries it out, once.  Separate passes: forward one (scores), dH pass two (scores
+    recomputed, dH), dE pass one (dE; its own second recomputation of the scores is overhead and does not count);
+    hidden sizes up to 128 run the dH and the dE pass in one launch (tile_bwd, three).  With fuse_dH the forward launch
+    carries scores and dH (two), and the backward pass's one recomputation of the scores happens in the dE launch (two).
     Row-gather kernels: the candidate rows of every valid position (K+1 rows of d elements), the ids, H, and for the
     backward pass dH and every dE row written once.
     """
@@ -72,7 +74,7 @@ def kernel_work(w, family):
     if family in ("tile_dh", "tile_fdh"):   # scores + dH; the fused forward + dH pass (fuse_dH) is the same two
         return "mfma", 2 * gemm
     if family == "tile_de":
-        return "mfma", gemm
+        return "mfma", (2 * gemm if fused else gemm)
     if family == "tile_bwd":   # dH and dE pass in one launch
         return "mfma", 3 * gemm
     if family == "dh_scale":   # U read, dH written (fp32 both), grad_loss
@@ -241,7 +243,7 @@ def measure(w, args, *, headline: bool) -> dict:
     dom_ms = fam[dominant][0] / steps
 
     flops, bytes_min = algorithmic_work(w)
-    bound, work = kernel_work(w, dominant)
+    bound, work = kernel_work(w, dominant, fused=bool(fuse))
     if bound == "mfma":
         peak = PEAK_MFMA_BF16_TFLOPS if w.in_dtype == "bf16" else PEAK_F32_VALU_TFLOPS
         roof = {"bound": "mfma", "kernel": dominant, "achieved": work / (dom_ms * 1e-3) / 1e12, "peak": peak,
