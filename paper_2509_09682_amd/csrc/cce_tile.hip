@@ -61,7 +61,16 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(PrepArgs p)
             }
         } else if (p.mask) {  // i0 is a multiple of 1024, the mask is 16-byte aligned
             const uint4 *m16 = reinterpret_cast<const uint4 *>(p.mask);
-            for (int64_t c = tid; c < i0 / 16; c += kPrepThreads) {
+            const int64_t n16 = i0 / 16;
+            int64_t c = tid;
+            for (; c + 3 * kPrepThreads < n16; c += 4 * kPrepThreads) {  // four loads in flight: the walk is a chain of latencies
+                const uint4 v0 = m16[c], v1 = m16[c + kPrepThreads], v2 = m16[c + 2 * kPrepThreads], v3 = m16[c + 3 * kPrepThreads];
+                before += nonzero_bytes(v0.x) + nonzero_bytes(v0.y) + nonzero_bytes(v0.z) + nonzero_bytes(v0.w);
+                before += nonzero_bytes(v1.x) + nonzero_bytes(v1.y) + nonzero_bytes(v1.z) + nonzero_bytes(v1.w);
+                before += nonzero_bytes(v2.x) + nonzero_bytes(v2.y) + nonzero_bytes(v2.z) + nonzero_bytes(v2.w);
+                before += nonzero_bytes(v3.x) + nonzero_bytes(v3.y) + nonzero_bytes(v3.z) + nonzero_bytes(v3.w);
+            }
+            for (; c < n16; c += kPrepThreads) {
                 const uint4 v = m16[c];
                 before += nonzero_bytes(v.x) + nonzero_bytes(v.y) + nonzero_bytes(v.z) + nonzero_bytes(v.w);
             }
@@ -117,9 +126,8 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(PrepArgs p)
             }
         }
         __syncthreads();
-        for (int64_t k = tid; k < p.K; k += kPrepThreads) {
-            const int32_t id = p.neg[k];
-            if (id < 0) continue;  // flagged by the range check below; never equal to a valid target
+        auto count_hit = [&](int32_t id) {
+            if (id < 0) return;  // flagged by the range check below; never equal to a valid target
             uint32_t h = hash_id(id, kTgtSlots);
             for (int probe = 0; probe < kTgtSlots; ++probe) {
                 const int32_t key = hkey[h];
@@ -130,7 +138,16 @@ __global__ __launch_bounds__(kPrepThreads) void prep_kernel(PrepArgs p)
                 if (key == -1) break;
                 h = (h + 1) & (kTgtSlots - 1);
             }
+        };
+        int64_t k = tid;
+        for (; k + 3 * kPrepThreads < p.K; k += 4 * kPrepThreads) {  // ids of four rounds fetched together
+            const int32_t id0 = p.neg[k], id1 = p.neg[k + kPrepThreads], id2 = p.neg[k + 2 * kPrepThreads], id3 = p.neg[k + 3 * kPrepThreads];
+            count_hit(id0);
+            count_hit(id1);
+            count_hit(id2);
+            count_hit(id3);
         }
+        for (; k < p.K; k += kPrepThreads) count_hit(p.neg[k]);
         __syncthreads();
         if (valid) p.cnt[i] = hcnt[my_slot];
     }
