@@ -845,7 +845,19 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                 gp_t gp;
                 uint4 ob[RD][BS];
                 const uint16_t *arow = tile + sb * 32 * D;
+                // PAIRED (register-lean addressing): the two reads of a batch are the ones whose swizzled offsets agree
+                // (pieces kk and kk + NA; output blocks mb and mb + NT), so that one XOR serves both and the rest of the
+                // address is an immediate: a third of the vector instructions of a step were such XORs.
+                constexpr bool PAIRED = LEAN && BS == 2 && KK == 2 * NA && MBH == 2 * NT;
+                auto s_piece = [&](int b, int i) { return PAIRED ? b + i * NA : b * BS + i; };
+                auto p_block = [&](int b, int i) { return PAIRED ? (b % (MBH / BS)) + i * NT : (b % (MBH / BS)) * BS + i; };
                 auto read_batch = [&](int b, uint4 (&dst)[BS]) {
+                    if constexpr (PAIRED) {
+                        const uint16_t *q = lds_at(arow, a_base, ((b * 2) & SM) * 8, 0);
+                        dst[0] = *reinterpret_cast<const uint4 *>(q);
+                        dst[1] = *reinterpret_cast<const uint4 *>(q + NA * 16);
+                        return;
+                    }
 #pragma unroll
                     for (int i = 0; i < BS; ++i) {
                         const int kk = b * BS + i;
@@ -865,7 +877,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     for (int i = 0; i < BS; ++i)
 #pragma unroll
                         for (int g = 0; g < XG; ++g)
-                            sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ob[b % RD][i]), as_bf16x8(xr[g][b * BS + i]), sv[g], 0, 0, 0);
+                            sv[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ob[b % RD][i]), as_bf16x8(xr[g][s_piece(b, i)]), sv[g], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                     if (b + RD < NB_S) read_batch(b + RD, ob[b % RD]);
                 }
@@ -875,6 +887,18 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                     auto read_tr_batch = [&](int b, s16x8 (&dst)[BS]) {
                         const int k2 = b / (MBH / BS);
                         const uint16_t *tbase = tile + (sb * 32 + k2 * 16) * D + half * (MBH * 32);
+                        if constexpr (PAIRED) {
+                            const int mb0 = b % (MBH / BS);
+                            const uint16_t *q0 = lds_at(tbase, t_base0, ((mb0 * 4) & SM) * 8, 0);
+                            const uint16_t *q1 = lds_at(tbase, t_base1, ((mb0 * 4) & SM) * 8, 0);
+#pragma unroll
+                            for (int i = 0; i < BS; ++i) {
+                                const s16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q0 + i * (NT * 32)));
+                                const s16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(q1 + i * (NT * 32)));
+                                dst[i] = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+                            }
+                            return;
+                        }
 #pragma unroll
                         for (int i = 0; i < BS; ++i) {
                             const int mb = (b % (MBH / BS)) * BS + i;
@@ -900,7 +924,7 @@ __device__ __forceinline__ void tile_body(const TileArgs a, const int64_t block_
                         const int k2 = b / (MBH / BS);
 #pragma unroll
                         for (int i = 0; i < BS; ++i) {
-                            const int mb = (b % (MBH / BS)) * BS + i;
+                            const int mb = p_block(b, i);
                             bf16x8 av;
                             __builtin_memcpy(&av, &tb[b % RD][i], 16);
 #pragma unroll
