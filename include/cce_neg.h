@@ -97,10 +97,13 @@ typedef struct {
                                        flag AND reuse_forward_prep = 1 then writes dH_i = grad_loss_i U_i and computes the
                                        scores once more for dE only: four products of the size of the score matrix per
                                        step instead of five, two exponentials per score instead of three.  Set it the
-                                       same way in the size query, the forward and the backward descriptor.  Matrix-core
-                                       path only (bf16, shared or full mode, d in {64,128,256}); ignored elsewhere, and
-                                       by a backward call without reuse_forward_prep or with filter_eps > 0 (those run
-                                       the dH pass as without the flag).  A forward-only caller leaves it 0. */
+                                       same way in the size query, the forward and the backward descriptor.  On the
+                                       row-gather kernels (fp32, other hidden sizes, per-position negatives) the forward
+                                       call sums the weighted candidate rows while it has them in registers for the
+                                       score, and the backward call gathers no candidate row for dH (same 4 N d bytes).
+                                       Ignored for per-position negatives beyond the inverted index (2^31 pairs and
+                                       more), and by a backward call without reuse_forward_prep or with filter_eps > 0
+                                       (those run the dH pass as without the flag).  A forward-only caller leaves it 0. */
 } cce_desc;
 
 /* Bytes of device workspace both calls need for this descriptor.  Returns 0 for an invalid descriptor.
@@ -117,7 +120,7 @@ typedef struct {
  *                              4 bytes per table row, 4 per position and at most 32 MiB of bucket counts.  Catalogues
  *                              of more than 2^22 items whose pairs exceed B: a 256-byte header (they keep the atomic
  *                              row adds of Alg. 2);
- *   otherwise:                 a 256-byte header;
+ *   otherwise:                 a 256-byte header (with fuse_dH: 4 + 4 d bytes per position more, also in per-position mode);
  *   shared mode, in addition:  4 bytes per negative (where the *_sampled calls write the list they draw).
  * No score, probability or gradient-coefficient matrix is ever stored: the workspace holds indices and per-position
  * scalars only.  The same workspace may be reused by later calls on the same stream. */

@@ -155,7 +155,7 @@ Params make_params(const cce_desc *d, const void *H, const void *E, const int32_
 // built and used up in slices of the item-id range: 12 bytes per pair of ONE slice (at most max(2^22, N K / 8) pairs),
 // one word per item, one per position, and the (bucket, block) counts of the first sort level (32 MiB at most).
 struct PpLayout {
-    size_t coef, cursor, block_sums, pairs, tmp, part_hist, hot_list, plan, total;
+    size_t coef, cursor, block_sums, pairs, tmp, part_hist, hot_list, plan, U, total;
 };
 PpLayout make_pp_layout(const cce_desc *d)
 {
@@ -174,6 +174,7 @@ PpLayout make_pp_layout(const cce_desc *d)
     L.part_hist = off;   off += align256(n_hist * 4);
     L.hot_list = off;    off += align256(invert_hot_capacity(d->N, d->K) * 16);
     L.plan = off;        off += align256((2 * n_buckets + (size_t)invert_plan_words()) * 4);
+    L.U = off;           off += d->fuse_dH ? align256((size_t)d->N * (size_t)d->d * 4) : 0;  // fused forward pass
     L.total = off;
     return L;
 }
@@ -183,6 +184,39 @@ bool use_inverted(const cce_desc *d)
     // catalogues beyond the sliced build (more than 2048 * 2048 items) whose pairs do not fit one slice.
     if (d->neg_mode != CCE_NEG_PER_POSITION || d->K <= 0 || d->N * (int64_t)d->K >= 0x7fffffffLL) return false;
     return invert_partitioned(d->V) || invert_slices(d->N, d->K) == 1;
+}
+
+// The forward call of the row-gather family forms the hidden-state gradient as well (fuse_dH): every mode but
+// per-position negatives too many for the inverted index (their backward pass gathers the rows anyway, for dE).
+bool fused_gather(const cce_desc *d)
+{
+    return d->fuse_dH != 0 && !use_tile(d) && (d->neg_mode != CCE_NEG_PER_POSITION || use_inverted(d));
+}
+// ... and what it keeps in the workspace where there is no inverted index: p+ - 1 per position and the rows U.
+struct PlainLayout {
+    size_t coef, U, total;
+};
+PlainLayout make_plain_layout(const cce_desc *d)
+{
+    PlainLayout L{};
+    size_t off = kHeaderBytes;
+    L.coef = off;  off += align256((size_t)d->N * 4);
+    L.U = off;     off += align256((size_t)d->N * (size_t)d->d * 4);
+    L.total = off;
+    return L;
+}
+void set_fused_gather(const cce_desc *d, void *workspace, Params &p)
+{
+    char *ws = static_cast<char *>(workspace);
+    if (use_inverted(d)) {
+        const PpLayout L = make_pp_layout(d);
+        p.coef = reinterpret_cast<float *>(ws + L.coef);
+        p.U = reinterpret_cast<float *>(ws + L.U);
+    } else {
+        const PlainLayout L = make_plain_layout(d);
+        p.coef = reinterpret_cast<float *>(ws + L.coef);
+        p.U = reinterpret_cast<float *>(ws + L.U);
+    }
 }
 
 TileArgs make_tile_args(const cce_desc *d, const Layout &L, const void *H, const void *E, const int32_t *tgt,
@@ -252,7 +286,7 @@ size_t shared_ids_offset(const cce_desc *d)
 {
     if (use_tile(d)) return make_layout(d).total;
     if (use_inverted(d)) return make_pp_layout(d).total;
-    return kHeaderBytes;
+    return fused_gather(d) ? make_plain_layout(d).total : kHeaderBytes;
 }
 
 cce_status check_sampler(const cce_desc *d, const cce_sampler *s)
@@ -423,6 +457,7 @@ cce_status forward_impl(const cce_desc *desc, const Sampler &smp, const void *H,
     p.loss = loss;
     p.lse = lse;
     p.smp = smp;
+    if (cce::fused_gather(desc)) cce::set_fused_gather(desc, workspace, p);  // the kernel that also files U and p+ - 1
     const hipError_t e = cce::launch_gather(false, desc->in_dtype == CCE_BF16, p, stream);
     return e == hipSuccess ? CCE_OK : CCE_ERR_HIP;
 }
@@ -481,10 +516,36 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
     p.dH = dH;
     p.dE = dE;
     p.smp = smp;
+    const bool bf16 = desc->in_dtype == CCE_BF16;
+    const bool scatter = bf16 && cce::tile_supports_d(desc->d);  // the aggregated scatter of the correct items exists
+    // fuse_dH: the forward call left U and p+ - 1; no candidate row is gathered for dH
+    const bool fused = cce::fused_gather(desc) && desc->reuse_forward_prep;
+    cce::TileArgs t{};
+    if (scatter) {
+        t.H = static_cast<const uint16_t *>(H);
+        t.tgt = tgt;
+        t.pos_mask = mask;
+        t.dE = dE;
+        t.N = desc->N;
+        t.V = desc->V;
+        t.d = desc->d;
+        t.validate = desc->validate_indices ? 1 : 0;
+    }
+    if (fused) {
+        cce::set_fused_gather(desc, workspace, p);
+        if (cce::launch_gather_scale(bf16, !scatter, p, stream) != hipSuccess) return CCE_ERR_HIP;
+        t.coef = p.coef;       // short of the upstream gradient:
+        t.g_separate = 1;      // the scatter multiplies by grad_loss itself
+        t.g = grad_loss;
+    }
     if (!cce::use_inverted(desc)) {
         // Shared negatives or the full catalogue: the position-major pass yields dH and the correct items' dE rows; the
         // rows of the shared candidates, which every position updates, come from a candidate-major pass.
         const bool shared_rows = desc->neg_mode != CCE_NEG_PER_POSITION;
+        if (fused) {  // (never per-position here)
+            if (scatter && cce::launch_pos_scatter(t, stream) != hipSuccess) return CCE_ERR_HIP;
+            return cce::launch_shared_dE(bf16, p, stream) == hipSuccess ? CCE_OK : CCE_ERR_HIP;
+        }
         if (shared_rows) p.skip_neg_dE = 1;
         if (cce::launch_gather(true, desc->in_dtype == CCE_BF16, p, stream) != hipSuccess) return CCE_ERR_HIP;
         if (shared_rows && cce::launch_shared_dE(desc->in_dtype == CCE_BF16, p, stream) != hipSuccess) return CCE_ERR_HIP;
@@ -494,23 +555,12 @@ cce_status backward_impl(const cce_desc *desc, const Sampler &smp, const void *H
     // comes from the inverted-index pass, dE of the correct items from the aggregated scatter where it exists.
     const cce::PpLayout L = cce::make_pp_layout(desc);
     char *ws = static_cast<char *>(workspace);
-    const bool bf16 = desc->in_dtype == CCE_BF16;
-    const bool scatter = bf16 && cce::tile_supports_d(desc->d);
-    p.skip_neg_dE = 1;
-    p.skip_pos_dE = scatter ? 1 : 0;
-    p.coef = reinterpret_cast<float *>(ws + L.coef);
-    if (cce::launch_gather(true, bf16, p, stream) != hipSuccess) return CCE_ERR_HIP;
-    cce::TileArgs t{};
-    if (scatter) {
-        t.H = static_cast<const uint16_t *>(H);
-        t.tgt = tgt;
-        t.pos_mask = mask;
+    if (!fused) {
+        p.skip_neg_dE = 1;
+        p.skip_pos_dE = scatter ? 1 : 0;
+        p.coef = reinterpret_cast<float *>(ws + L.coef);
+        if (cce::launch_gather(true, bf16, p, stream) != hipSuccess) return CCE_ERR_HIP;
         t.coef = p.coef;
-        t.dE = dE;
-        t.N = desc->N;
-        t.V = desc->V;
-        t.d = desc->d;
-        t.validate = desc->validate_indices ? 1 : 0;
     }
     cce::InvertArgs ia{};
     ia.H = H;

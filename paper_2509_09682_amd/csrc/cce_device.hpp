@@ -28,7 +28,10 @@ struct Params {
     // backward of the row-gather family when dE of the negatives is produced by the inverted-index pass instead:
     int32_t skip_neg_dE;    // 1: no dE atomics for negatives
     int32_t skip_pos_dE;    // 1: no dE atomics for the correct item either (the aggregated scatter adds it)
-    float *coef;            // [N] out: g_i (p+_i - 1), coefficient of the correct item (nullable)
+    float *coef;            // [N] out: g_i (p+_i - 1), coefficient of the correct item (nullable); the fused forward pass
+                            // files p+_i - 1 there, short of the upstream gradient
+    float *U;               // [N,d] fp32, fused forward pass: sum_j softmax_ij E_cij - E_tgt_i (Eq. 6 left with grad LSE = 1);
+                            // the backward call scales it by grad_loss
     Sampler smp;            // per-position mode, kind != 0: the negatives are drawn in the kernel, neg is not read
 };
 

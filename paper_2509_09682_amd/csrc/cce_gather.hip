@@ -185,6 +185,187 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_gather_kernel(Params 
     }
 }
 
+
+// Forward pass that also forms the hidden-state gradient short of the upstream gradient (fuse_dH on this family): the
+// candidate rows are in registers once, for the score; the same visit adds softmax-weighted rows up (an online softmax
+// carried through Eq. 6 left), so the backward call gathers no candidate row for dH at all.  Each lane group takes the
+// score of its first live candidate as the reference of its exponentials (any reference gives the same result as long
+// as nothing leaves the float range) and never looks at a maximum again; the true maximum is tracked on the side, and
+// if a sum did leave the range (a later score more than about 69 nats above the reference) the wavefront walks its
+// candidates once more against that maximum.  Groups are merged at the end, each scaled from its own reference.
+template <typename T, int LPR, int IDS>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void fwd_fused_gather_kernel(Params p)
+{
+    constexpr int RPI = 64 / LPR;
+    constexpr int kUnroll = unroll_of<T>();
+    static_assert(kWindow % (RPI * kUnroll) == 0, "a step never straddles two windows");
+    __shared__ int32_t window[IDS != IDS_DIRECT ? kWavesPerBlock : 1][IDS != IDS_DIRECT ? kWindow : 1];
+    int32_t *win = window[IDS != IDS_DIRECT ? (threadIdx.x >> 6) : 0];
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int grp = lane / LPR;
+    const int64_t i = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (i >= p.N) return;
+
+    bool valid = (p.mask == nullptr) || (p.mask[i] != 0);
+    int32_t ti = 0;
+    bool bad = false;
+    if (valid) {
+        ti = p.tgt[i];
+        if (p.validate && (ti < 0 || (int64_t)ti >= p.V)) { bad = true; valid = false; }
+    }
+    if (!valid) {  // the backward call writes the zero dH row of a padded position itself
+        if (lane == 0) {
+            p.loss[i] = 0.f;
+            p.lse[i] = 0.f;
+            if (bad) atomicOr(p.status, 1);
+        }
+        return;
+    }
+
+    const T *Hp = static_cast<const T *>(p.H);
+    const T *Ep = static_cast<const T *>(p.E);
+    const bool col_ok = (c * 8 < p.d);
+    float h[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) h[t] = 0.f;
+    if (col_ok) load8(Hp + i * (int64_t)p.d + c * 8, h);
+
+    const int64_t n_cand = (p.neg_mode == CCE_NEG_FULL) ? p.V : (int64_t)p.K + 1;
+    float ref = -INFINITY, s = 0.f, o_pos = 0.f, top = -INFINITY;  // top: largest live score this lane group has seen
+    float acc[8];
+    // one walk over the candidates; FIXED: the reference is given (second walk), else the first live score of the group
+    auto walk = [&](auto fixed_tag) {
+        constexpr bool FIXED = decltype(fixed_tag)::value;
+        s = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+        for (int64_t j0 = 0; j0 < n_cand; j0 += RPI * kUnroll) {
+            if (IDS != IDS_DIRECT && (j0 & (kWindow - 1)) == 0) refill_window<IDS>(p, i, j0, win);
+            Cand cd[kUnroll];
+            RawChunk<T> raw[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                cd[u] = candidate<IDS>(p, i, j0 + u * RPI + grp, n_cand, ti, bad, win);
+                raw[u].clear();
+                if (cd[u].live && col_ok) raw[u].load(Ep + cd[u].id * (int64_t)p.d + c * 8);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float e[8];
+                raw[u].widen(e);
+                float part = 0.f;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) part = fmaf(h[t], e[t], part);
+                const float o = group_sum<LPR>(part);
+                if (cd[u].live) {
+                    if (cd[u].is_pos) o_pos = o;
+                    if (!FIXED) {
+                        top = fmaxf(top, o);
+                        if (ref == -INFINITY) ref = o;
+                    }
+                    const float w = fast_exp(o - ref);
+                    s += w;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) acc[t] = fmaf(w, e[t], acc[t]);
+                }
+            }
+        }
+    };
+    walk(std::false_type{});
+    {   // did any sum of the wavefront leave the float range?  (the rows are sums of at most s * max|e|)
+        const bool over = !(s < 1.0e30f);
+        if (__any(over)) {
+            float M = top;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+            ref = M;  // every group live or not: exp(o - M) <= 1
+            walk(std::true_type{});
+        }
+    }
+    // merge the lane groups: each holds (reference, sum, row) of its share of the candidates
+    float M = ref;  // -inf for a group that saw no live candidate
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    const float scale = (ref == -INFINITY) ? 0.f : fast_exp(ref - M);
+    s *= scale;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] *= scale;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        s += __shfl_xor(s, off, 64);
+        o_pos += __shfl_xor(o_pos, off, 64);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] += __shfl_xor(acc[t], off, 64);
+    }
+    if (p.validate && __any(bad)) {
+        if (lane == 0) atomicOr(p.status, 1);
+    }
+    const float l = M + fast_log(s);
+    const float inv = 1.f / s;
+    if (lane == 0) {
+        p.lse[i] = l;
+        p.loss[i] = l - o_pos;
+        p.coef[i] = fast_exp(o_pos - l) - 1.f;  // coefficient of the correct item, short of the upstream gradient
+    }
+    if (grp == 0 && col_ok) {
+        float et[8];
+        load8(Ep + (int64_t)ti * p.d + c * 8, et);
+        float4 *out = reinterpret_cast<float4 *>(p.U + i * (int64_t)p.d + c * 8);
+        out[0] = make_float4(fmaf(acc[0], inv, -et[0]), fmaf(acc[1], inv, -et[1]), fmaf(acc[2], inv, -et[2]), fmaf(acc[3], inv, -et[3]));
+        out[1] = make_float4(fmaf(acc[4], inv, -et[4]), fmaf(acc[5], inv, -et[5]), fmaf(acc[6], inv, -et[6]), fmaf(acc[7], inv, -et[7]));
+    }
+}
+
+// Backward side of the fused forward pass: dH_i = grad_loss_i U_i (zero rows for padded positions), eight columns per
+// thread; and, where no aggregated scatter exists for the hidden size, the correct items' rows
+// dE[tgt_i] += grad_loss_i (p+_i - 1) H_i by atomics, one wavefront per position.
+__global__ __launch_bounds__(256) void gather_scale_kernel(Params p)
+{
+    const int cpr = p.d / 8;  // d is a multiple of 8
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = idx / cpr;
+    const int c = (int)(idx % cpr);
+    if (i >= p.N) return;
+    bool valid = (p.mask == nullptr) || (p.mask[i] != 0);
+    if (valid && p.validate) {
+        const int32_t ti = p.tgt[i];
+        valid = ti >= 0 && (int64_t)ti < p.V;
+    }
+    float v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = 0.f;
+    if (valid) {
+        const float g = p.g ? p.g[i] : 1.f;
+        load8(p.U + i * (int64_t)p.d + c * 8, v);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= g;
+    }
+    if (p.dH_bf16) {
+        *reinterpret_cast<uint4 *>(static_cast<uint16_t *>(p.dH) + i * (int64_t)p.d + c * 8) =
+            make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+    } else {
+        float4 *out = reinterpret_cast<float4 *>(static_cast<float *>(p.dH) + i * (int64_t)p.d + c * 8);
+        out[0] = make_float4(v[0], v[1], v[2], v[3]);
+        out[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pos_rows_dE_kernel(Params p)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= p.N) return;
+    if (p.mask && p.mask[i] == 0) return;
+    const int32_t ti = p.tgt[i];
+    if (p.validate && (ti < 0 || (int64_t)ti >= p.V)) return;
+    const float G = (p.g ? p.g[i] : 1.f) * p.coef[i];
+    const T *hrow = static_cast<const T *>(p.H) + i * (int64_t)p.d;
+    float *row = p.dE + (int64_t)ti * p.d;
+    for (int col = lane; col < p.d; col += 64) unsafeAtomicAdd(row + col, G * load1(hrow + col));
+}
+
 // ATOMIC_DE = false: dE comes from other passes (inverted index, aggregated scatter); this pass yields dH and the
 // correct-item coefficients only.
 template <typename T, int LPR, bool ATOMIC_DE, int IDS>
@@ -432,6 +613,8 @@ hipError_t launch_pair(bool backward, const Params &p, hipStream_t stream)
             hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, false, IDS>), grid, block, 0, stream, p);
         else if (backward)
             hipLaunchKernelGGL((bwd_gather_kernel<T, LPR, true, IDS>), grid, block, 0, stream, p);
+        else if (p.U)
+            hipLaunchKernelGGL((fwd_fused_gather_kernel<T, LPR, IDS>), grid, block, 0, stream, p);
         else
             hipLaunchKernelGGL((fwd_gather_kernel<T, LPR, IDS>), grid, block, 0, stream, p);
     };
@@ -458,6 +641,20 @@ hipError_t launch_by_width(bool backward, const Params &p, hipStream_t stream)
 hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream)
 {
     return bf16 ? launch_by_width<uint16_t>(backward, p, stream) : launch_by_width<float>(backward, p, stream);
+}
+
+hipError_t launch_gather_scale(bool bf16, bool pos_rows, const Params &p, hipStream_t stream)
+{
+    if (p.N == 0) return hipSuccess;
+    ProfScope prof(PROF_DH_SCALE, stream);
+    const int64_t n = p.N * (int64_t)(p.d / 8);
+    hipLaunchKernelGGL(gather_scale_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !pos_rows) return e;
+    const dim3 grid((unsigned)((p.N + 3) / 4));
+    if (bf16) hipLaunchKernelGGL(pos_rows_dE_kernel<uint16_t>, grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(pos_rows_dE_kernel<float>, grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_shared_dE(bool bf16, const Params &p, hipStream_t stream)

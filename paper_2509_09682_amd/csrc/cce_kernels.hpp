@@ -13,6 +13,9 @@ enum { kHdrStatus = 0, kHdrTotal = 1, kHdrDone = 2, kHdrNValid = 3, kHdrHot = 4 
 hipError_t launch_gather(bool backward, bool bf16, const Params &p, hipStream_t stream);
 // dE of the negatives shared by all positions (shared list or full catalogue), candidate-major; row-gather family
 hipError_t launch_shared_dE(bool bf16, const Params &p, hipStream_t stream);
+// backward side of the fused forward pass of the row-gather family (Params::U set by the forward call): dH = grad_loss * U,
+// and with pos_rows the correct items' dE rows by atomics
+hipError_t launch_gather_scale(bool bf16, bool pos_rows, const Params &p, hipStream_t stream);
 
 // ---- matrix-core family: bf16 inputs, shared negatives or full catalogue
 struct PrepArgs {

@@ -9,7 +9,7 @@ import pytest
 from oracle import cce_oracle as O
 from oracle.compare import tensor_rel
 from test_gpu_parity import (FULL_SIZE_BARS, TOL_BF16, check_against_oracle, rounding_model_excess)
-from workloads import NEG_FULL, NEG_SHARED, config, make_workload
+from workloads import NEG_FULL, NEG_PER_POSITION, NEG_SHARED, config, make_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -156,3 +156,71 @@ def test_fused_full_size_c2_against_full_oracle():
     errs = check_against_oracle(w, _run(w, algo=0), TOL_BF16)
     b = FULL_SIZE_BARS[2]
     assert errs["dH"] <= b[0] and errs["dE"] <= b[1] and errs["dH_row"] <= b[2] and errs["dE_row"] <= b[3], (errs, b)
+
+
+# ---- the same flag on the row-gather kernels (fp32 inputs, other hidden sizes, per-position negatives): the forward
+#      call sums the weighted candidate rows while it has them for the score; the backward call gathers none for dH
+
+def _run_gather(w, **kw):
+    from hip_harness import run_hip
+    import paper_2509_09682_amd as P
+
+    kw.setdefault("algo", P.CCE_ALGO_GATHER)
+    return run_hip(w, fuse_dH=True, reuse_prep=True, **kw)
+
+
+@pytest.mark.parametrize("mode", [NEG_SHARED, NEG_PER_POSITION, NEG_FULL])
+@pytest.mark.parametrize("dtype,d", [("f32", 40), ("f32", 64), ("bf16", 128), ("bf16", 320)])
+def test_fused_row_gather_family(mode, dtype, d):
+    import paper_2509_09682_amd as P
+
+    K = 0 if mode == NEG_FULL else 203
+    V = 1003 if mode == NEG_FULL else 157
+    w = make_workload(f"fused_gather_m{mode}_{dtype}_d{d}", 7, 61, d, V, K, dtype, mode, 900 + d + mode, pad="right",
+                      pad_len_lo=20, g_kind="random", e_sigma=0.1, tgt_dist="zipf")
+    for collide in ((0, 1) if mode != NEG_FULL else (1,)):
+        w.mask_collisions = collide
+        check_against_oracle(w, _run_gather(w), 2e-5)
+    out = _run_gather(w, dH_dtype=P.CCE_BF16 if dtype == "bf16" else P.CCE_F32, use_mask=False, g=None, repeat_backward=2)
+    out["dE"] = out["dE"] * 0.5                                   # U and p+ - 1 survive a backward call
+    w.mask[:] = 1
+    check_against_oracle(w, out, 2e-5, g=None, dH_tol=TOL_BF16 if dtype == "bf16" else None)
+
+
+def test_fused_row_gather_reduced_c3_and_c1():
+    for idx, scale in ((3, 0.05), (1, 1.0)):
+        w = config(idx, scale=scale, g_kind="random")
+        check_against_oracle(w, _run_gather(w), 2e-5)
+
+
+def test_fused_row_gather_scores_that_outgrow_the_first_reference():
+    """Every lane group takes its first live score as reference; here later candidates score up to 150 nats higher, the
+    sums leave the float range and the wavefront walks its candidates again against the true maximum."""
+    d, K = 64, 300
+    w = make_workload("fused_gather_climb", 3, 40, d, 2000, K, "f32", NEG_PER_POSITION, 77, pad="bernoulli", pad_p=0.1,
+                      g_kind="random", e_sigma=0.05)
+    rng = np.random.default_rng(5)
+    E = w.E.reshape(w.V, d).copy()
+    H = w.H.reshape(w.N, d)
+    neg = w.neg.reshape(w.N, K)
+    for i in range(0, w.N, 3):                       # a third of the positions get a steep candidate late in the list
+        j = int(rng.integers(K // 2, K))
+        v = int(neg[i, j])
+        h = H[i].astype(np.float64)
+        E[v] = (150.0 * h / float(h @ h)).astype(np.float32)   # <h_i, e_v> = 150
+    w.E = E.reshape(w.E.shape)
+    errs = check_against_oracle(w, _run_gather(w), 2e-5)
+    assert errs["lse"] <= 2e-5
+
+
+def test_fused_row_gather_equals_the_separate_passes():
+    from hip_harness import run_hip
+    import paper_2509_09682_amd as P
+
+    w = make_workload("fused_gather_vs_plain", 9, 83, 128, 4000, 97, "bf16", NEG_PER_POSITION, 4243, pad="bernoulli",
+                      pad_p=0.35, g_kind="random", e_sigma=0.1, tgt_dist="zipf")
+    a = _run_gather(w)
+    b = run_hip(w, algo=P.CCE_ALGO_GATHER)
+    assert np.max(np.abs(a["lse"] - b["lse"])) <= 2e-6 * np.max(np.abs(b["lse"]))
+    assert tensor_rel(a["dH"], b["dH"]) <= 1e-5 and tensor_rel(a["dE"], b["dE"]) <= 1e-5
+    assert np.all(a["dH"][w.mask == 0] == 0)
