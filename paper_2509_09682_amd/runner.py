@@ -84,11 +84,16 @@ def sample_hip(w, smp):
     return out.cpu().numpy()
 
 
-def run_hip_sampled(w, smp, *, algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32):
-    """Forward + backward through the *_sampled calls (w.neg is ignored).  Same result dict as run_hip."""
+def run_hip_sampled(w, smp, *, algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32, fuse_dH: bool = False):
+    """Forward + backward through the *_sampled calls (w.neg is ignored).  Same result dict as run_hip.
+    fuse_dH: the forward call also forms the hidden-state gradient; the backward call reuses what it left."""
     H, E, tgt, _, mask = to_device(w)
     desc = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
-                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, algo=algo)
+                       dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, algo=algo,
+                       fuse_dH=1 if fuse_dH else 0)
+    desc_bwd = P.make_desc(w.N, w.V, w.d, w.K, P.CCE_F32 if w.in_dtype == "f32" else P.CCE_BF16, w.neg_mode,
+                           dH_dtype=dH_dtype, mask_target_collisions=w.mask_collisions, algo=algo,
+                           fuse_dH=1 if fuse_dH else 0, reuse_forward_prep=1 if fuse_dH else 0)
     ws = P.new_workspace(desc)
     loss = torch.full((w.N,), float("nan"), device="cuda")
     lse = torch.full((w.N,), float("nan"), device="cuda")
@@ -96,7 +101,7 @@ def run_hip_sampled(w, smp, *, algo=P.CCE_ALGO_AUTO, dH_dtype=P.CCE_F32):
     g_t = torch.from_numpy(w.g).to("cuda")
     dH = torch.full((w.N, w.d), float("nan"), device="cuda", dtype=torch.bfloat16 if dH_dtype == P.CCE_BF16 else torch.float32)
     dE = torch.zeros((w.V, w.d), device="cuda")
-    P.cce_neg_backward_sampled(desc, smp, H, E, tgt, mask, lse, g_t, dH, dE, ws)
+    P.cce_neg_backward_sampled(desc_bwd, smp, H, E, tgt, mask, lse, g_t, dH, dE, ws)
     status = P.cce_neg_index_status(ws)
     torch.cuda.synchronize()
     return dict(loss=loss.cpu().numpy(), lse=lse.cpu().numpy(), dH=dH.float().cpu().numpy(), dE=dE.cpu().numpy(),

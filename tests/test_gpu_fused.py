@@ -224,3 +224,23 @@ def test_fused_row_gather_equals_the_separate_passes():
     assert np.max(np.abs(a["lse"] - b["lse"])) <= 2e-6 * np.max(np.abs(b["lse"]))
     assert tensor_rel(a["dH"], b["dH"]) <= 1e-5 and tensor_rel(a["dE"], b["dE"]) <= 1e-5
     assert np.all(a["dH"][w.mask == 0] == 0)
+
+
+@pytest.mark.parametrize("mode,dtype,d", [(NEG_PER_POSITION, "bf16", 128), (NEG_PER_POSITION, "f32", 40), (NEG_SHARED, "f32", 64),
+                                          (NEG_SHARED, "bf16", 256)])
+def test_fused_sampled_calls(mode, dtype, d):
+    """Negatives drawn inside the kernels, with the fused forward pass: the row-gather kernels redraw the ids in the one
+    pass that is left; shared lists (drawn once into the workspace) follow the stored-list paths of either family."""
+    import dataclasses
+
+    from hip_harness import device_sampler, run_hip_sampled
+    from oracle import sampler as S
+
+    w = make_workload(f"fused_sampled_m{mode}_{dtype}_d{d}", 9, 37, d, 3000, 130, dtype, mode, 1234 + d, pad="bernoulli",
+                      pad_p=0.2, g_kind="random", e_sigma=0.1, tgt_dist="zipf")
+    smp, keep = device_sampler(S.UNIFORM, 777, 3)
+    ids = S.sample_negatives(S.UNIFORM, 777, 3, w.N, w.K, w.V, per_position=(mode == NEG_PER_POSITION))
+    w_ref = dataclasses.replace(w, neg=ids)
+    out = run_hip_sampled(w, smp, fuse_dH=True)
+    assert out["status"] == 0
+    check_against_oracle(w_ref, out, TOL_BF16 if (dtype == "bf16" and mode == NEG_SHARED) else 2e-5)
