@@ -100,6 +100,37 @@ template <> struct RawChunk<float> {
     }
 };
 
+// Streaming accesses (data used once): loads and stores marked non-temporal leave the L2 lines they touch first in
+// line for eviction, so that a small operand that IS reused (the hidden states in the item pass) stays resident.
+typedef float f32x4_nt __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load(const float4 *p)
+{
+    const f32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_nt *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store(float4 *p, float4 v)
+{
+    f32x4_nt w;
+    w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
+    __builtin_nontemporal_store(w, reinterpret_cast<f32x4_nt *>(p));
+}
+__device__ __forceinline__ int32_t stream_load(const int32_t *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void stream_load8(const float *p, float (&v)[8])
+{
+    const float4 a = stream_load(reinterpret_cast<const float4 *>(p)), b = stream_load(reinterpret_cast<const float4 *>(p) + 1);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void stream_load8(const uint16_t *p, float (&v)[8])
+{
+    const u32x4_nt r = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt *>(p));
+    v[0] = bf16_lo(r.x); v[1] = bf16_hi(r.x);
+    v[2] = bf16_lo(r.y); v[3] = bf16_hi(r.y);
+    v[4] = bf16_lo(r.z); v[5] = bf16_hi(r.z);
+    v[6] = bf16_lo(r.w); v[7] = bf16_hi(r.w);
+}
+
 __device__ __forceinline__ float load1(const float *p) { return *p; }
 __device__ __forceinline__ float load1(const uint16_t *p) { return __uint_as_float(static_cast<uint32_t>(*p) << 16); }
 

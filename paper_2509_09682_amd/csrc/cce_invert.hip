@@ -403,7 +403,7 @@ __device__ __forceinline__ void walk_segment(const InvertArgs &a, const float (&
         RawChunk<T> raw[U];
         float lse[U], g[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) pos[u] = (r + u < r_end) ? a.pairs[r + u] : -1;
+        for (int u = 0; u < U; ++u) pos[u] = (r + u < r_end) ? stream_load(a.pairs + r + u) : -1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             raw[u].clear();
@@ -483,18 +483,18 @@ __global__ __launch_bounds__(kThreads) void item_dE_kernel(InvertArgs a)
     const bool mine = r < r_end && col_ok;
     float4 *row = reinterpret_cast<float4 *>(a.dE + (mine ? v : 0) * (int64_t)a.d + c * 8);
     float4 dx = make_float4(0.f, 0.f, 0.f, 0.f), dy = dx;
-    if (mine) {
-        load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
-        dx = row[0];
-        dy = row[1];
+    if (mine) {  // used once each: they must not push the hidden states out of L2
+        stream_load8(static_cast<const T *>(a.E) + v * (int64_t)a.d + c * 8, e);
+        dx = stream_load(row);
+        dy = stream_load(row + 1);
     }
     walk_segment<T, LPR>(a, e, r, r_end, col_ok, c, acc);
     // the row belongs to this lane group alone: plain read-modify-write
     if (mine) {
         dx.x += acc[0]; dx.y += acc[1]; dx.z += acc[2]; dx.w += acc[3];
         dy.x += acc[4]; dy.y += acc[5]; dy.z += acc[6]; dy.w += acc[7];
-        row[0] = dx;
-        row[1] = dy;
+        stream_store(row, dx);
+        stream_store(row + 1, dy);
     }
     }  // item groups of this block
 }
